@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused LM-head log-prob + policy-loss forward+backward on one MI355X.
+
+One step = one call of rl_policy_loss_fwd_bwd (prep, forward, advantage, loss, backward) over
+one seeded synthetic rollout batch that is already resident in HBM.  Prints ONE JSON line:
+rollout tokens/s (mask=1 rows only), the MFMA roofline of the dominant contraction kernel
+(timed live with HIP events on the library's stream) and the float64 oracle timed on the
+host cores on a bounded token-sub-sampled sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 32, "7b": 512, "long": 2048, "32b": 2048}
+
+
+def cpu_baseline(name: str, objective: str):
+    """Time the oracle, as it stands, on a token-sub-sampled instance of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import policy_oracle as orc
+    from paper_2603_16435_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    div = CPU_SAMPLE_LEN_DIV[name]
+    b = synth.make_rollouts(name, "cpu", "packed", len_div=div)
+
+    def bits(t):
+        t = t.contiguous()
+        return t.view(torch.int16).numpy() if t.dtype == torch.bfloat16 else t.numpy()
+
+    c = b.cfg
+    t0 = time.perf_counter()
+    orc.policy_loss_fwd_bwd(orc.GRPO if objective == "grpo" else orc.FLOW, bits(b.hidden), bits(b.weight),
+                            bits(b.token_ids), bits(b.mask), bits(b.cu_seqlens), bits(b.group_idx), bits(b.rewards),
+                            bits(b.old_logprob), bits(b.ref_logprob), bits(b.log_z), c.P, clip_eps=c.clip_eps,
+                            kl_coef=c.kl_coef, beta=c.beta, adv_eps=c.adv_eps, adv_std_ddof=c.adv_std_ddof)
+    dt = time.perf_counter() - t0
+    return {"value": b.T / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"same config, every sequence cut to ceil(len/{div}) tokens: {b.T} tokens, "
+                      f"full H={c.H} V={c.V}, fwd+bwd in float64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="7b", choices=["tiny", "small", "7b", "long", "32b"])
+    ap.add_argument("--objective", default="grpo", choices=["grpo", "flow"])
+    ap.add_argument("--layout", default="padded", choices=["padded", "packed"])
+    ap.add_argument("--chunk-rows", type=int, default=0)
+    ap.add_argument("--len-div", type=int, default=1, help="shorten every sequence (debug / profiling runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
+              "Sharding is design-only (whole prompts per GPU, or vocab-parallel W).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_16435_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    b = synth.make_rollouts(a.config, dev, a.layout, len_div=a.len_div)
+    cfg = b.cfg
+    obj = binding.OBJECTIVES[a.objective]
+    batch = binding.make_batch(b.hidden, b.weight, b.token_ids, b.mask, b.cu_seqlens, b.group_idx, b.rewards,
+                               b.old_logprob, b.ref_logprob, b.log_z, cfg.P)
+    prm = binding.make_params(cfg.clip_eps, cfg.kl_coef, cfg.beta, cfg.adv_eps, cfg.adv_std_ddof, a.chunk_rows)
+    plan = binding.PolicyLossPlan(batch, prm, dev, b.hidden.dtype, backward=True)
+
+    for _ in range(a.warmup):
+        plan.run(obj)
+    torch.cuda.synchronize()
+    binding.rl_profile_enable(True)
+    binding.rl_profile_read()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        res = plan.run(obj)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = binding.rl_profile_read()
+    binding.rl_profile_enable(False)
+
+    T = int(res.stats_dict()["n_tokens"])
+    loss = float(res.loss.item())
+    assert T == b.T and loss == loss, (T, b.T, loss)
+    ms_step = dt / a.steps * 1e3
+    tok_s = T * a.steps / dt
+    thv = float(T) * cfg.H * cfg.V
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
+    # dominant kernel: the contraction class with the largest share of the step
+    gemms = {k: prof[k] for k in ("gemm_fwd", "gemm_ds", "gemm_dx", "gemm_dw")}
+    dom = max(gemms, key=lambda k: gemms[k][0])
+    dom_ms, dom_n = gemms[dom]
+    flops_per_step_class = 2.0 * thv                       # each of the four contractions: 2*T*H*V
+    achieved = flops_per_step_class * a.steps / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    kernels = {k: {"ms_per_step": v[0] / a.steps, "launches_per_step": v[1] / a.steps,
+                   "tflops": (2.0 * thv * a.steps / (v[0] * 1e-3) / 1e12) if (k in gemms and v[0] > 0) else None}
+               for k, v in prof.items()}
+    out = {
+        "metric": "rollout tokens/sec, fused logprob+policy-loss fwd+bwd; % bf16 MFMA peak",
+        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{a.config}: P={cfg.P} G={cfg.G} len U[{cfg.len_lo},{cfg.len_hi}] H={cfg.H} V={cfg.V} "
+                               f"{cfg.dtype}, {a.layout} rows R={b.R}, real tokens T={T}, objective={a.objective}"
+                               + (f", len_div={a.len_div}" if a.len_div != 1 else ""),
+                   "objective": a.objective, "layout": a.layout, "T": T, "R": b.R, "H": cfg.H, "V": cfg.V,
+                   "chunk_rows": a.chunk_rows or binding.lib().rl_default_chunk_rows()},
+        "mfma_frac_6THV": 6.0 * thv / (dt / a.steps) / 1e12 / peak,
+        "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
+        "roofline": {"bound": "mfma", "kernel": f"gemm_nt_kernel ({dom})", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": int(dom_n)},
+        "kernels": kernels,
+        "loss": loss,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(a.config, a.objective)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,162 @@
+/*
+ * rl_policy.h - C ABI of the fused LM-head log-prob + policy-loss library (MI355X / gfx950).
+ *
+ * What it computes (problem statement of the benchmark contract; the mounted paper has
+ * no passage on it): for every response token t of a group of sampled responses,
+ *     z_t   = W x_t                      (never stored)
+ *     lse_t = log sum_v exp z_t[v],      logp_t = z_t[y_t] - lse_t
+ * then the group-relative advantage A_i = (r_i - mean_g)/(std_g + adv_eps) over the G
+ * rollouts of a prompt, then one of two objectives
+ *     GRPO:  loss = (1/B) sum_i (1/|y_i|) sum_t [ -min(rho_t A_i, clip(rho_t,1-e,1+e) A_i)
+ *                                                 + kl_coef (exp(d_t) - d_t - 1) ],
+ *            rho_t = exp(logp_t - old_t),  d_t = ref_t - logp_t
+ *     FLOW:  loss = (1/B) sum_i w_i delta_i^2,
+ *            delta_i = logZ_g(i) + (1/|y_i|) sum_t (logp_t - ref_t) - beta A_i,
+ *            w_i = clip(exp(sum_t (logp_t - old_t)), 1-e, 1+e) held constant
+ * and the backward pass  c_t = dloss/dlogp_t,  dS[t,v] = c_t (1[v=y_t] - softmax(z_t)[v]),
+ * dX = dS W, dW = dS^T X, with the logits recomputed tile by tile (T x V is never stored;
+ * only a chunk of dS in the input precision is staged between the three contractions).
+ *
+ * Conventions
+ *  - Every pointer in rl_batch / rl_outputs and the workspace is a DEVICE pointer owned by
+ *    the caller; rl_batch / rl_params / rl_outputs structs themselves live on the HOST.
+ *  - The library allocates nothing, keeps no pointer after return, and never synchronises:
+ *    all work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
+ *    stream); outputs are valid once the stream reaches that point.
+ *  - Row-major everywhere.  hidden is [R,H], weight is [V,H] (LM head, no bias); row t of
+ *    hidden is the state that predicts token_ids[t] (the caller did the shift).
+ *  - Sequence i owns rows [cu_seqlens[i], cu_seqlens[i+1]); cu_seqlens[0]=0, cu_seqlens[B]=R,
+ *    non-decreasing.  A row counts iff mask[t] != 0.  Padded layouts simply mask the tail.
+ *  - Masked rows: logprob = lse = 0, d_hidden row = 0, no contribution anywhere.
+ *  - Host-checkable errors (null pointers, sizes, dtype, objective, clip range, workspace
+ *    size) are returned before anything is launched.  Data errors found on the device
+ *    (token id outside [0,V), group index outside [0,P), decreasing cu_seqlens) never
+ *    cause an out-of-bounds access: the offending row / sequence is treated as masked /
+ *    empty and counted in rl_stats.
+ *  - Results are bit-reproducible run to run: no floating-point atomics are used.
+ *  - bf16 inputs need H % 8 == 0 (16-byte rows); f32 inputs need H % 4 == 0.
+ */
+#ifndef RL_POLICY_H
+#define RL_POLICY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rl_status {
+  RL_OK = 0,
+  RL_ERR_NULL = 1,        /* a required pointer is NULL                         */
+  RL_ERR_SHAPE = 2,       /* a size is non-positive, too large or misaligned    */
+  RL_ERR_DTYPE = 3,       /* unknown rl_dtype                                   */
+  RL_ERR_RANGE = 4,       /* objective / clip_eps / ddof out of range           */
+  RL_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than needed  */
+  RL_ERR_HIP = 6          /* a HIP launch failed (see hipGetLastError)          */
+} rl_status;
+
+typedef enum rl_objective { RL_OBJ_GRPO = 0, RL_OBJ_FLOW = 1 } rl_objective;
+typedef enum rl_dtype { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
+
+typedef struct rl_batch {
+  int64_t R;                    /* rows (tokens incl. masked ones), 1 <= R < 2^31 - 2^16 */
+  int32_t H, V, B, P;           /* hidden, vocab, sequences, prompts                     */
+  int32_t dtype;                /* rl_dtype of hidden, weight, d_hidden                  */
+  int32_t reserved;
+  const void*    hidden;        /* [R,H]                                                 */
+  const void*    weight;        /* [V,H]                                                 */
+  const int32_t* token_ids;     /* [R]   sampled token y_t in [0,V)                      */
+  const uint8_t* mask;          /* [R]   1 = response token                              */
+  const int32_t* cu_seqlens;    /* [B+1]                                                 */
+  const int32_t* group_idx;     /* [B]   prompt index g(i) in [0,P)   (loss call only)   */
+  const float*   rewards;       /* [B]                                (loss call only)   */
+  const float*   old_logprob;   /* [R]   log-prob under the sampling policy  (loss only) */
+  const float*   ref_logprob;   /* [R]   log-prob under the reference policy (loss only) */
+  const float*   log_z;         /* [P]   per-prompt log partition; FLOW only, else NULL  */
+} rl_batch;
+
+typedef struct rl_params {
+  float   clip_eps;             /* in (0,1)                                              */
+  float   kl_coef;              /* GRPO only                                             */
+  float   beta;                 /* FLOW only: reward scale                               */
+  float   adv_eps;              /* added to the group std                                */
+  int32_t adv_std_ddof;         /* 0 (population std) or 1                               */
+  int32_t chunk_rows;           /* rows of dS staged at once; 0 = library default.       */
+                                /* rounded up to a multiple of 256; sizes the workspace  */
+} rl_params;
+
+typedef struct rl_stats {       /* device struct written by the loss call                */
+  int32_t n_tokens;             /* number of rows that counted (T)                       */
+  int32_t n_clip_hi;            /* GRPO: tokens with A>0, rho>1+e; FLOW: sequences with the weight on the upper bound */
+  int32_t n_clip_lo;            /* GRPO: tokens with A<0, rho<1-e; FLOW: ... lower bound */
+  int32_t n_bad_token;          /* mask=1 rows dropped because token id was out of range */
+  int32_t n_bad_group;          /* sequences dropped because group_idx was out of range  */
+  int32_t n_bad_seq;            /* sequences treated as empty (cu_seqlens decreasing / out of [0,R]) */
+  int32_t reserved[2];
+} rl_stats;
+
+typedef struct rl_outputs {     /* NULL = not wanted, except loss                        */
+  float*    loss;               /* [1]                                                   */
+  float*    seq_loss;           /* [B]                                                   */
+  float*    logprob;            /* [R]                                                   */
+  float*    lse;                /* [R]                                                   */
+  float*    advantages;         /* [B]                                                   */
+  int32_t*  seq_len;            /* [B]   |y_i|                                           */
+  float*    coeff;              /* [R]   c_t = dloss/dlogp_t                             */
+  void*     d_hidden;           /* [R,H] input dtype; d_hidden and d_weight NULL together skips the backward */
+  float*    d_weight;           /* [V,H] f32, overwritten                                */
+  float*    d_log_z;            /* [P]   zero for GRPO                                   */
+  rl_stats* stats;              /* [1]                                                   */
+} rl_outputs;
+
+/* Bytes of device workspace the two calls below need for this batch shape (host only; reads
+ * R, H, V, B, P, dtype and params->chunk_rows; params may be NULL = defaults; want_backward
+ * = 0 sizes it for rl_token_logprob / loss-only calls).  The workspace must be 256-byte
+ * aligned.  Its contents on entry are irrelevant and on return unspecified. */
+rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params,
+                             int32_t want_backward, size_t* bytes);
+
+/* Forward only: logprob[R] and lse[R] (either may be NULL, not both) for the rows with
+ * mask != 0; reads hidden, weight, token_ids, mask, cu_seqlens (B may be 1 with
+ * cu_seqlens = {0,R}).  Used to score rollouts under the old / reference policies. */
+rl_status rl_token_logprob(const rl_batch* batch, float* logprob, float* lse,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* The whole path: log-prob, per-sequence length-normalised sums, group advantage, loss and
+ * per-token coefficient, and (if d_hidden and d_weight are given) the backward pass. */
+rl_status rl_policy_loss_fwd_bwd(const rl_batch* batch, const rl_params* params,
+                                 int32_t objective, const rl_outputs* outputs,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+const char* rl_status_string(int32_t status);
+
+/* Optional timing of the library's own launches, for benchmarks (not thread-safe; the only
+ * place the library creates objects of its own: HIP events, kept for reuse).  While enabled,
+ * every group of launches of the two calls above is bracketed by a pair of events recorded on
+ * the caller's stream.  rl_profile_read waits for the recorded events, adds up elapsed
+ * milliseconds and bracket counts per class since the previous read, and clears the list. */
+enum { RL_PROF_PREP = 0,       /* counts, scan, compaction, output zero-fill            */
+       RL_PROF_GEMM_FWD = 1,   /* forward logits contraction + online partial softmax   */
+       RL_PROF_COMBINE = 2,    /* partials -> lse, logp                                 */
+       RL_PROF_LOSS = 3,       /* advantage, per-sequence loss, final reduce            */
+       RL_PROF_TRANSPOSE = 4,  /* W^T, X^T chunks, zeroing masked dX rows               */
+       RL_PROF_GEMM_DS = 5,    /* recomputed logits -> dS, dS^T                         */
+       RL_PROF_GEMM_DX = 6,    /* dX = dS W                                             */
+       RL_PROF_GEMM_DW = 7,    /* dW += dS^T X                                          */
+       RL_PROF_CLASSES = 8 };
+typedef struct rl_profile {     /* host struct */
+  double  ms[RL_PROF_CLASSES];
+  int64_t launches[RL_PROF_CLASSES];
+} rl_profile;
+void rl_profile_enable(int32_t on);
+rl_status rl_profile_read(rl_profile* out);
+
+/* Library version (major*100 + minor) and the chunk size used when chunk_rows = 0. */
+int32_t rl_version(void);
+int32_t rl_default_chunk_rows(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RL_POLICY_H */

@@ -1,0 +1,252 @@
+"""Thin ctypes binding over the C ABI declared in include/rl_policy.h.
+
+Argument marshalling only: torch tensors supply device memory and the current stream, every
+step of the path runs in the HIP library.  There is no fallback: if the library has not been
+built (`python -m paper_2603_16435_amd.build`) loading fails with an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librl_policy.so")
+
+RL_OBJ_GRPO, RL_OBJ_FLOW = 0, 1
+RL_F32, RL_BF16 = 0, 1
+OBJECTIVES = {"grpo": RL_OBJ_GRPO, "flow": RL_OBJ_FLOW}
+
+
+class rl_batch(C.Structure):
+    _fields_ = [("R", C.c_int64), ("H", C.c_int32), ("V", C.c_int32), ("B", C.c_int32), ("P", C.c_int32),
+                ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("hidden", C.c_void_p), ("weight", C.c_void_p), ("token_ids", C.c_void_p), ("mask", C.c_void_p),
+                ("cu_seqlens", C.c_void_p), ("group_idx", C.c_void_p), ("rewards", C.c_void_p),
+                ("old_logprob", C.c_void_p), ("ref_logprob", C.c_void_p), ("log_z", C.c_void_p)]
+
+
+class rl_params(C.Structure):
+    _fields_ = [("clip_eps", C.c_float), ("kl_coef", C.c_float), ("beta", C.c_float), ("adv_eps", C.c_float),
+                ("adv_std_ddof", C.c_int32), ("chunk_rows", C.c_int32)]
+
+
+class rl_stats(C.Structure):
+    _fields_ = [("n_tokens", C.c_int32), ("n_clip_hi", C.c_int32), ("n_clip_lo", C.c_int32),
+                ("n_bad_token", C.c_int32), ("n_bad_group", C.c_int32), ("n_bad_seq", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
+
+
+class rl_outputs(C.Structure):
+    _fields_ = [("loss", C.c_void_p), ("seq_loss", C.c_void_p), ("logprob", C.c_void_p), ("lse", C.c_void_p),
+                ("advantages", C.c_void_p), ("seq_len", C.c_void_p), ("coeff", C.c_void_p),
+                ("d_hidden", C.c_void_p), ("d_weight", C.c_void_p), ("d_log_z", C.c_void_p), ("stats", C.c_void_p)]
+
+
+PROF_CLASSES = ("prep", "gemm_fwd", "combine", "loss", "transpose", "gemm_ds", "gemm_dx", "gemm_dw")
+
+
+class rl_profile(C.Structure):
+    _fields_ = [("ms", C.c_double * 8), ("launches", C.c_int64 * 8)]
+
+
+STATS_FIELDS = ("n_tokens", "n_clip_hi", "n_clip_lo", "n_bad_token", "n_bad_group", "n_bad_seq")
+
+_lib = None
+
+
+class RlError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"rl_policy: status {status}: {msg}")
+        self.status = status
+
+
+def lib() -> C.CDLL:
+    """Load the in-tree library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_16435_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.rl_workspace_bytes.argtypes = [C.POINTER(rl_batch), C.POINTER(rl_params), C.c_int32, C.POINTER(C.c_size_t)]
+        L.rl_workspace_bytes.restype = C.c_int
+        L.rl_token_logprob.argtypes = [C.POINTER(rl_batch), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rl_token_logprob.restype = C.c_int
+        L.rl_policy_loss_fwd_bwd.argtypes = [C.POINTER(rl_batch), C.POINTER(rl_params), C.c_int32,
+                                             C.POINTER(rl_outputs), C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rl_policy_loss_fwd_bwd.restype = C.c_int
+        L.rl_status_string.argtypes = [C.c_int32]
+        L.rl_status_string.restype = C.c_char_p
+        L.rl_profile_enable.argtypes = [C.c_int32]
+        L.rl_profile_enable.restype = None
+        L.rl_profile_read.argtypes = [C.POINTER(rl_profile)]
+        L.rl_profile_read.restype = C.c_int
+        L.rl_version.restype = C.c_int32
+        L.rl_default_chunk_rows.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _check(st: int):
+    if st != 0:
+        raise RlError(st, lib().rl_status_string(st).decode())
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, numel=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name} must have {numel} elements, got {t.numel()}")
+    return t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return RL_F32
+    if t.dtype == torch.bfloat16:
+        return RL_BF16
+    raise ValueError(f"hidden/weight must be float32 or bfloat16, got {t.dtype}")
+
+
+def make_batch(hidden, weight, token_ids, mask, cu_seqlens, group_idx=None, rewards=None,
+               old_logprob=None, ref_logprob=None, log_z=None, P: Optional[int] = None) -> rl_batch:
+    R, H = hidden.shape
+    V = weight.shape[0]
+    if weight.shape[1] != H or weight.dtype != hidden.dtype:
+        raise ValueError("weight must be [V,H] with the dtype of hidden")
+    B = cu_seqlens.numel() - 1
+    if P is None:
+        P = log_z.numel() if log_z is not None else 1
+    b = rl_batch()
+    b.R, b.H, b.V, b.B, b.P = R, H, V, B, P
+    b.dtype = _dtype_code(hidden)
+    b.hidden = _ptr(hidden, name="hidden")
+    b.weight = _ptr(weight, name="weight")
+    b.token_ids = _ptr(token_ids, torch.int32, R, "token_ids")
+    b.mask = _ptr(mask, torch.uint8, R, "mask")
+    b.cu_seqlens = _ptr(cu_seqlens, torch.int32, B + 1, "cu_seqlens")
+    b.group_idx = _ptr(group_idx, torch.int32, B, "group_idx")
+    b.rewards = _ptr(rewards, torch.float32, B, "rewards")
+    b.old_logprob = _ptr(old_logprob, torch.float32, R, "old_logprob")
+    b.ref_logprob = _ptr(ref_logprob, torch.float32, R, "ref_logprob")
+    b.log_z = _ptr(log_z, torch.float32, P, "log_z")
+    return b
+
+
+def rl_workspace_bytes(batch: rl_batch, params: Optional[rl_params], want_backward: bool) -> int:
+    n = C.c_size_t(0)
+    _check(lib().rl_workspace_bytes(C.byref(batch), C.byref(params) if params is not None else None,
+                                    1 if want_backward else 0, C.byref(n)))
+    return n.value
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+    off = (-ws.data_ptr()) % 256
+    return ws[off:off + nbytes]
+
+
+def _stream_handle() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def rl_token_logprob(hidden, weight, token_ids, mask, cu_seqlens=None, workspace=None):
+    """Forward only: (logprob[R], lse[R]) float32; masked rows read 0."""
+    R = hidden.shape[0]
+    dev = hidden.device
+    if cu_seqlens is None:
+        cu_seqlens = torch.tensor([0, R], dtype=torch.int32, device=dev)
+    b = make_batch(hidden, weight, token_ids, mask, cu_seqlens)
+    need = rl_workspace_bytes(b, None, False)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    logp = torch.empty(R, dtype=torch.float32, device=dev)
+    lse = torch.empty(R, dtype=torch.float32, device=dev)
+    _check(lib().rl_token_logprob(C.byref(b), logp.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
+                                  _stream_handle()))
+    return logp, lse
+
+
+@dataclass
+class LossResult:
+    loss: torch.Tensor
+    seq_loss: torch.Tensor
+    logprob: torch.Tensor
+    lse: torch.Tensor
+    advantages: torch.Tensor
+    seq_len: torch.Tensor
+    coeff: torch.Tensor
+    d_hidden: Optional[torch.Tensor]
+    d_weight: Optional[torch.Tensor]
+    d_log_z: torch.Tensor
+    stats: torch.Tensor          # int32[8]: see STATS_FIELDS
+
+    def stats_dict(self):
+        v = self.stats.cpu().tolist()
+        return dict(zip(STATS_FIELDS, v))
+
+
+class PolicyLossPlan:
+    """Pre-allocated outputs + workspace for repeated calls on one batch shape (timing loops)."""
+
+    def __init__(self, batch: rl_batch, params: rl_params, device, hidden_dtype, backward=True):
+        R, H, V, B, P = batch.R, batch.H, batch.V, batch.B, batch.P
+        f32 = dict(dtype=torch.float32, device=device)
+        self.res = LossResult(
+            loss=torch.empty(1, **f32), seq_loss=torch.empty(B, **f32), logprob=torch.empty(R, **f32),
+            lse=torch.empty(R, **f32), advantages=torch.empty(B, **f32),
+            seq_len=torch.empty(B, dtype=torch.int32, device=device), coeff=torch.empty(R, **f32),
+            d_hidden=torch.empty((R, H), dtype=hidden_dtype, device=device) if backward else None,
+            d_weight=torch.empty((V, H), **f32) if backward else None,
+            d_log_z=torch.empty(P, **f32), stats=torch.zeros(8, dtype=torch.int32, device=device))
+        self.ws = _workspace(rl_workspace_bytes(batch, params, backward), device)
+        o = rl_outputs()
+        r = self.res
+        o.loss, o.seq_loss, o.logprob, o.lse = r.loss.data_ptr(), r.seq_loss.data_ptr(), r.logprob.data_ptr(), r.lse.data_ptr()
+        o.advantages, o.seq_len, o.coeff = r.advantages.data_ptr(), r.seq_len.data_ptr(), r.coeff.data_ptr()
+        o.d_hidden = r.d_hidden.data_ptr() if backward else None
+        o.d_weight = r.d_weight.data_ptr() if backward else None
+        o.d_log_z, o.stats = r.d_log_z.data_ptr(), r.stats.data_ptr()
+        self.out = o
+        self.batch, self.params = batch, params
+
+    def run(self, objective: int, stream: Optional[int] = None) -> LossResult:
+        _check(lib().rl_policy_loss_fwd_bwd(C.byref(self.batch), C.byref(self.params), objective, C.byref(self.out),
+                                            self.ws.data_ptr(), self.ws.numel(),
+                                            _stream_handle() if stream is None else stream))
+        return self.res
+
+
+def make_params(clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0, chunk_rows=0) -> rl_params:
+    return rl_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows)
+
+
+def rl_policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards,
+                           old_logprob, ref_logprob, log_z=None, P: Optional[int] = None,
+                           clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
+                           chunk_rows=0, backward=True) -> LossResult:
+    """One pass of the whole path.  `objective` is "grpo" | "flow" (or the enum value)."""
+    obj = OBJECTIVES[objective] if isinstance(objective, str) else int(objective)
+    b = make_batch(hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards, old_logprob, ref_logprob, log_z, P)
+    prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows)
+    plan = PolicyLossPlan(b, prm, hidden.device, hidden.dtype, backward)
+    return plan.run(obj)
+
+
+def rl_profile_enable(on: bool) -> None:
+    lib().rl_profile_enable(1 if on else 0)
+
+
+def rl_profile_read() -> dict:
+    """{class: (ms, brackets)} accumulated since the last read (waits for the recorded events)."""
+    pr = rl_profile()
+    _check(lib().rl_profile_read(C.byref(pr)))
+    return {name: (pr.ms[i], pr.launches[i]) for i, name in enumerate(PROF_CLASSES)}

@@ -1,0 +1,181 @@
+// epilogues.h - what each contraction does with its accumulators while they are in registers.
+//
+// Orientation.  The logits contraction is run "vocab-major": A = W (rows = vocab entries),
+// B = X (rows = tokens), so that in the 32x32 accumulator layout a lane owns ONE token column
+// and 16 vocab rows per block.  The softmax reductions over the vocabulary are then mostly
+// in-register; the only cross-lane step is between lanes l and l+32 (one shuffle), and the
+// only cross-wavefront step is between the WAVES_M wavefronts stacked along the vocabulary.
+#pragma once
+#include "gemm_nt.h"
+
+namespace rlk {
+
+template <class T> __device__ inline float fast_exp(float x);
+template <> __device__ inline float fast_exp<bf16_t>(float x) { return __expf(x); }
+template <> __device__ inline float fast_exp<float>(float x) { return expf(x); }
+
+// ---- forward: per-token partial (max, sum exp) over this tile's vocab range + target gather
+//      z_t[y_t] is written by the single lane that holds vocab row y_t of token t.
+template <class T>
+struct EpiFwd {
+  const int* ids_c;     // [chunk-global compact row] sampled token
+  float* zy_c;          // [compact row] target logit
+  float2* part;         // [tiles_m(V)][ldp] partial (max, sumexp) per token
+  int ldp;              // = chunk rows
+  int V;
+
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
+    float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
+    const float NEG = -__builtin_inff();
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj) {
+      const int n = c.n0 + acc_col(bj, c.lane);
+      const bool valid = n < c.Nv;
+      const int y = valid ? ids_c[d.chunk_start + n] : -1;
+      float mx = NEG;
+#pragma unroll
+      for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int m = c.m0 + acc_row(bi, i, c.lane);
+          float v = acc[bi][bj][i];
+          if (m == y) zy_c[d.chunk_start + n] = v;
+          v = (m < V) ? v : NEG;
+          acc[bi][bj][i] = v;
+          mx = fmaxf(mx, v);
+        }
+      const float ms = (mx == NEG) ? 0.f : mx;
+      float sm = 0.f;
+#pragma unroll
+      for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sm += fast_exp<T>(acc[bi][bj][i] - ms);
+      const float mx2 = __shfl_xor(mx, 32), sm2 = __shfl_xor(sm, 32);
+      const float mm = fmaxf(mx, mx2);
+      const float mms = (mm == NEG) ? 0.f : mm;
+      sm = sm * fast_exp<T>(mx - mms) + sm2 * fast_exp<T>(mx2 - mms);
+      if (c.lane < 32) red[c.wm * BN + (n - c.tile_n * BN)] = make_float2(mm, sm);
+    }
+    __syncthreads();
+    if (c.tid < BN) {
+      const int n = c.tile_n * BN + c.tid;
+      if (n < c.Nv) {
+        float2 r = red[c.tid];
+#pragma unroll
+        for (int w = 1; w < WAVES_M; ++w) {
+          const float2 o = red[w * BN + c.tid];
+          const float mm = fmaxf(r.x, o.x);
+          const float mms = (mm == NEG) ? 0.f : mm;
+          r.y = r.y * fast_exp<T>(r.x - mms) + o.y * fast_exp<T>(o.x - mms);
+          r.x = mm;
+        }
+        part[(int64_t)c.tile_m * ldp + n] = r;
+      }
+    }
+  }
+};
+
+template <class T> struct Pack4;
+template <> struct Pack4<bf16_t> {
+  __device__ static void store(bf16_t* p, float a, float b, float c, float d) {
+    bf16x4 v; v[0] = (bf16_t)a; v[1] = (bf16_t)b; v[2] = (bf16_t)c; v[3] = (bf16_t)d;
+    *reinterpret_cast<bf16x4*>(p) = v;
+  }
+};
+template <> struct Pack4<float> {
+  __device__ static void store(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+  }
+};
+
+// ---- backward, stage 1: recomputed logits -> dS = c_t (1[v=y_t] - exp(z - lse_t)), formed in
+//      f32 (subtraction and scaling before rounding) and stored in the input precision twice:
+//      token-major dS[t][v] (operand of dX = dS W) and vocab-major dST[v][t] (operand of
+//      dW = dS^T X), so that both later contractions have K contiguous.
+template <class T>
+struct EpiDS {
+  const int* ids_c; const float* lse_c; const float* c_c;
+  T* dS;  int64_t ld_ds;    // [chunk rows][Vp]
+  T* dST; int64_t ld_dst;   // [Vp][chunk rows]
+  int V;
+
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj) {
+      const int n = c.n0 + acc_col(bj, c.lane);
+      const bool valid = n < c.Nv;
+      const int g = d.chunk_start + n;
+      const int y = valid ? ids_c[g] : -1;
+      const float lse = valid ? lse_c[g] : 0.f;
+      const float ct = valid ? c_c[g] : 0.f;
+#pragma unroll
+      for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int m = c.m0 + acc_row(bi, q * 4, c.lane);
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float p = fast_exp<T>(acc[bi][bj][q * 4 + e] - lse);
+            const float ds = ct * (((m + e) == y ? 1.f : 0.f) - p);
+            o[e] = (valid && (m + e) < V) ? ds : 0.f;
+          }
+          Pack4<T>::store(dS + (int64_t)n * ld_ds + m, o[0], o[1], o[2], o[3]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) dST[(int64_t)(m + e) * ld_dst + n] = (T)o[e];
+        }
+    }
+  }
+};
+
+// ---- backward, stage 2: dX tile -> rows scattered back to their original positions
+template <class T>
+struct EpiDX {
+  const int* row_map;   // compact row -> original row
+  T* dX; int64_t ldx; int H;
+
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int m = c.m0 + acc_row(bi, i, c.lane);
+        if (m >= c.Mv) continue;
+        const int64_t dst = row_map[d.chunk_start + m];
+#pragma unroll
+        for (int bj = 0; bj < NB; ++bj) {
+          const int n = c.n0 + acc_col(bj, c.lane);
+          if (n < H) dX[dst * ldx + n] = (T)acc[bi][bj][i];
+        }
+      }
+  }
+};
+
+// ---- backward, stage 3: dW tile, f32, overwritten by the first chunk and accumulated after
+struct EpiDW {
+  float* dW; int64_t ldw; int V, H; int accumulate;
+
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int m = c.m0 + acc_row(bi, i, c.lane);
+        if (m >= V) continue;
+#pragma unroll
+        for (int bj = 0; bj < NB; ++bj) {
+          const int n = c.n0 + acc_col(bj, c.lane);
+          if (n < H) {
+            float* p = dW + (int64_t)m * ldw + n;
+            *p = accumulate ? (*p + acc[bi][bj][i]) : acc[bi][bj][i];
+          }
+        }
+      }
+  }
+};
+
+}  // namespace rlk

@@ -1,0 +1,655 @@
+// rl_policy.hip - kernels of the O(T) stages and the C ABI of the library.
+//
+// Pipeline of rl_policy_loss_fwd_bwd (all on the caller's stream, no host sync):
+//   prep      : per-sequence counts -> scan -> ordered compaction of the rows that count
+//               (row_map, ids_c), masked rows of the outputs zeroed
+//   advantage : group mean / std of the rewards -> A_i
+//   forward   : per chunk of compacted rows: logits tiles (MFMA) -> partial (max,sumexp) per
+//               vocab tile + target logit -> combine -> lse_t, logp_t
+//   loss      : one workgroup per sequence: length-normalised sums, loss_i, c_t; final reduce
+//   backward  : W^T once; per chunk: X^T, recomputed logits -> dS / dS^T (input precision),
+//               dX = dS W (scattered to original rows), dW (+)= dS^T X
+// The number of real rows is only known on the device, so grids are sized for the upper
+// bound R and every kernel trims itself against the device-side count.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <utility>
+#include <vector>
+
+#include "../../include/rl_policy.h"
+#include "epilogues.h"
+#include "gemm_nt.h"
+
+namespace rlk {
+
+constexpr int kDefaultChunkRows = 16384;
+constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
+constexpr int kGemmThreads = kWavesM * kWavesN * 64;
+constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 KiB per CU
+
+struct Ctrl {            // device control block at the head of the workspace
+  int n_real;
+  int pad[15];
+};
+
+// ------------------------------------------------------------------ optional launch timing
+// When enabled (benchmarks only), each group of launches is bracketed by a pair of HIP events
+// on the caller's stream; rl_profile_read() folds the elapsed times per class.
+struct ProfRec { hipEvent_t a, b; int cls; };
+struct Profiler {
+  bool on = false;
+  std::vector<ProfRec> recs;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pool;
+};
+static Profiler g_prof;
+
+struct ProfScope {
+  hipStream_t s; hipEvent_t a{}, b{}; int cls; bool live;
+  ProfScope(int cls_, hipStream_t s_) : s(s_), cls(cls_), live(g_prof.on) {
+    if (!live) return;
+    if (!g_prof.pool.empty()) { a = g_prof.pool.back().first; b = g_prof.pool.back().second; g_prof.pool.pop_back(); }
+    else { if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { live = false; return; } }
+    (void)hipEventRecord(a, s);
+  }
+  ~ProfScope() {
+    if (!live) return;
+    (void)hipEventRecord(b, s);
+    g_prof.recs.push_back({a, b, cls});
+  }
+};
+
+// ------------------------------------------------------------------ small utilities
+__device__ inline int wave_prefix_count(bool flag, int lane, int& total) {
+  const unsigned long long b = __ballot(flag);
+  total = __popcll(b);
+  return __popcll(b & ((1ull << lane) - 1ull));
+}
+
+template <class V>
+__global__ void fill_kernel(V* p, int64_t n, V v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += step) p[i] = v;
+}
+
+template <class V>
+static void fill(V* p, int64_t n, V v, hipStream_t s) {
+  if (!p || n <= 0) return;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  fill_kernel<V><<<(int)blocks, 256, 0, s>>>(p, n, v);
+}
+
+__device__ inline double block_sum(double v, double* sh) {   // blockDim.x multiple of 64, <= 1024
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[w] = v;
+  __syncthreads();
+  double r = 0.0;
+  const int nw = blockDim.x >> 6;
+  for (int i = 0; i < nw; ++i) r += sh[i];                   // same order in every thread
+  return r;
+}
+
+// ------------------------------------------------------------------ prep
+// One workgroup per sequence: validate its row range and group index, count rows that count.
+__global__ void seq_count_kernel(const uint8_t* mask, const int32_t* ids, const int32_t* cu,
+                                 const int32_t* group_idx, int64_t R, int V, int P,
+                                 int32_t* seq_len, rl_stats* stats) {
+  const int i = blockIdx.x;
+  __shared__ int sh_cnt, sh_bad;
+  if (threadIdx.x == 0) { sh_cnt = 0; sh_bad = 0; }
+  __syncthreads();
+  const int64_t a = cu[i], b = cu[i + 1];
+  const bool seq_ok = (a >= 0 && a <= b && b <= R);
+  const bool grp_ok = (group_idx == nullptr) || (group_idx[i] >= 0 && group_idx[i] < P);
+  int cnt = 0, bad = 0;
+  if (seq_ok && grp_ok) {
+    for (int64_t r = a + threadIdx.x; r < b; r += blockDim.x) {
+      if (mask[r]) {
+        const int y = ids[r];
+        if (y >= 0 && y < V) ++cnt; else ++bad;
+      }
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) { cnt += __shfl_down(cnt, o); bad += __shfl_down(bad, o); }
+  if ((threadIdx.x & 63) == 0) { atomicAdd(&sh_cnt, cnt); atomicAdd(&sh_bad, bad); }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    seq_len[i] = sh_cnt;
+    if (stats) {
+      if (sh_bad) atomicAdd(&stats->n_bad_token, sh_bad);
+      if (!seq_ok) atomicAdd(&stats->n_bad_seq, 1);
+      if (!grp_ok) atomicAdd(&stats->n_bad_group, 1);
+    }
+  }
+}
+
+// Exclusive scan of seq_len over sequences (single workgroup of 1024), total -> ctrl.
+__global__ void seq_scan_kernel(const int32_t* seq_len, int B, int32_t* cstart, Ctrl* ctrl, rl_stats* stats) {
+  __shared__ int wsum[16];
+  __shared__ int carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int base = 0; base < B; base += 1024) {
+    const int i = base + threadIdx.x;
+    const int v = i < B ? seq_len[i] : 0;
+    int x = v;
+    for (int o = 1; o < 64; o <<= 1) { const int y = __shfl_up(x, o); if (lane >= o) x += y; }
+    if (lane == 63) wsum[w] = x;
+    __syncthreads();
+    int woff = 0;
+    for (int k = 0; k < w; ++k) woff += wsum[k];
+    if (i < B) cstart[i] = carry + woff + x - v;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry += woff + x;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    cstart[B] = carry;
+    ctrl->n_real = carry;
+    if (stats) stats->n_tokens = carry;
+  }
+}
+
+// Ordered compaction, one workgroup per sequence: the k-th counting row of sequence i becomes
+// compact row cstart[i]+k.  cpos[r] = compact position of original row r (left at -1 otherwise).
+__global__ void compact_kernel(const uint8_t* mask, const int32_t* ids, const int32_t* cu,
+                               const int32_t* seq_len, const int32_t* cstart, int V,
+                               int32_t* row_map, int32_t* ids_c, int32_t* cpos) {
+  const int i = blockIdx.x;
+  if (seq_len[i] == 0) return;
+  __shared__ int wsum[16];
+  __shared__ int carry;
+  if (threadIdx.x == 0) carry = cstart[i];
+  __syncthreads();
+  const int64_t a = cu[i], b = cu[i + 1];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int64_t base = a; base < b; base += blockDim.x) {
+    const int64_t r = base + threadIdx.x;
+    int y = 0;
+    bool f = false;
+    if (r < b && mask[r]) { y = ids[r]; f = (y >= 0 && y < V); }
+    int tot;
+    const int pre = wave_prefix_count(f, lane, tot);
+    if (lane == 0) wsum[w] = tot;
+    __syncthreads();
+    int woff = 0, all = 0;
+    for (int k = 0; k < nw; ++k) { if (k < w) woff += wsum[k]; all += wsum[k]; }
+    if (f) {
+      const int c = carry + woff + pre;
+      row_map[c] = (int)r; ids_c[c] = y; cpos[r] = c;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) carry += all;
+    __syncthreads();
+  }
+}
+
+template <class T>
+__global__ void zero_masked_rows_kernel(const int32_t* cpos, T* dX, int64_t R, int H) {
+  // one wavefront per row; rows that count are left alone (the dX epilogue writes them)
+  const int64_t r = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (r >= R || cpos[r] >= 0) return;
+  const int lane = threadIdx.x & 63;
+  uint4* p = reinterpret_cast<uint4*>(dX + r * H);
+  const int n16 = H * (int)sizeof(T) / 16;
+  for (int k = lane; k < n16; k += 64) p[k] = make_uint4(0, 0, 0, 0);
+}
+
+// ------------------------------------------------------------------ advantage
+// Thread per prompt p: mean and std of the rewards of its members, then A_i for each member.
+__global__ void advantage_kernel(const float* rewards, const int32_t* group_idx, int B, int P,
+                                 float adv_eps, int ddof, float* adv) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= P) return;
+  int n = 0; double s = 0.0;
+  for (int i = 0; i < B; ++i) if (group_idx[i] == p) { ++n; s += (double)rewards[i]; }
+  if (n == 0) return;
+  const double mu = s / n;
+  double inv = 0.0;
+  if (n - ddof > 0) {
+    double q = 0.0;
+    for (int i = 0; i < B; ++i) if (group_idx[i] == p) { const double e = (double)rewards[i] - mu; q += e * e; }
+    inv = 1.0 / (sqrt(q / (n - ddof)) + (double)adv_eps);
+  }
+  for (int i = 0; i < B; ++i) if (group_idx[i] == p) adv[i] = (float)(((double)rewards[i] - mu) * inv);
+}
+
+// ------------------------------------------------------------------ forward combine
+// Thread per compact row of the chunk: fold the per-vocab-tile partials into lse, logp.
+__global__ void lse_combine_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c,
+                                   const int32_t* row_map, const Ctrl* ctrl, int chunk_start, int chunk_rows,
+                                   float* lse_c, float* logp_c, float* lse_out, float* logp_out) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  int left = ctrl->n_real - chunk_start;
+  if (left > chunk_rows) left = chunk_rows;
+  if (n >= left) return;
+  float m = -__builtin_inff();
+  for (int t = 0; t < tiles_v; ++t) m = fmaxf(m, part[(int64_t)t * ldp + n].x);
+  double s = 0.0;
+  for (int t = 0; t < tiles_v; ++t) { const float2 v = part[(int64_t)t * ldp + n]; s += (double)v.y * exp((double)(v.x - m)); }
+  const float lse = (float)((double)m + log(s));
+  const int g = chunk_start + n;
+  const float lp = zy_c[g] - lse;
+  lse_c[g] = lse; logp_c[g] = lp;
+  const int r = row_map[g];
+  if (lse_out) lse_out[r] = lse;
+  if (logp_out) logp_out[r] = lp;
+}
+
+// ------------------------------------------------------------------ loss
+// One workgroup per sequence over its compact rows [cstart[i], cstart[i+1]).
+__global__ void seq_loss_kernel(int objective, const float* logp_c, const float* old_lp, const float* ref_lp,
+                                const int32_t* row_map, const int32_t* cstart, const float* adv,
+                                const int32_t* group_idx, const float* log_z, int B,
+                                float clip_eps, float kl_coef, float beta,
+                                float* seq_loss, float* gterm, float* c_c, float* coeff_out, rl_stats* stats) {
+  __shared__ double sh[16];
+  __shared__ int sh_hi, sh_lo;
+  const int i = blockIdx.x;
+  const int a = cstart[i], b = cstart[i + 1], n = b - a;
+  if (threadIdx.x == 0) { sh_hi = 0; sh_lo = 0; }
+  if (n <= 0) {
+    if (threadIdx.x == 0) { seq_loss[i] = 0.f; gterm[i] = 0.f; }
+    return;
+  }
+  const float A = adv[i];
+  const double inv_bn = 1.0 / ((double)B * (double)n);
+  if (objective == RL_OBJ_GRPO) {
+    double acc = 0.0; int hi = 0, lo = 0;
+    for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
+      const int r = row_map[k];
+      // per-token terms in f64: e^d - d - 1 cancels to ~d^2/2 and would lose digits in f32
+      const double lp = (double)logp_c[k];
+      const double rho = exp(lp - (double)old_lp[r]);
+      const double dd = (double)ref_lp[r] - lp;
+      const double ed = exp(dd);
+      const double lo_c = 1.0 - (double)clip_eps, hi_c = 1.0 + (double)clip_eps;
+      const double rc = fmin(fmax(rho, lo_c), hi_c);
+      const double Ad = (double)A;
+      const double l = -fmin(rho * Ad, rc * Ad) + (double)kl_coef * (ed - dd - 1.0);
+      const bool chi = (A > 0.f) && (rho > hi_c);
+      const bool clo = (A < 0.f) && (rho < lo_c);
+      hi += chi; lo += clo;
+      const double g = ((chi || clo) ? 0.0 : -Ad * rho) + (double)kl_coef * (1.0 - ed);
+      const float ct = (float)(g * inv_bn);
+      c_c[k] = ct;
+      if (coeff_out) coeff_out[r] = ct;
+      acc += l;
+    }
+    const double tot = block_sum(acc, sh);
+    for (int o = 32; o > 0; o >>= 1) { hi += __shfl_down(hi, o); lo += __shfl_down(lo, o); }
+    if ((threadIdx.x & 63) == 0) { if (hi) atomicAdd(&sh_hi, hi); if (lo) atomicAdd(&sh_lo, lo); }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      seq_loss[i] = (float)(tot / n); gterm[i] = 0.f;
+      if (stats) { if (sh_hi) atomicAdd(&stats->n_clip_hi, sh_hi); if (sh_lo) atomicAdd(&stats->n_clip_lo, sh_lo); }
+    }
+  } else {
+    double s_ref = 0.0, s_old = 0.0;
+    for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
+      const int r = row_map[k];
+      const float lp = logp_c[k];
+      s_ref += (double)(lp - ref_lp[r]);
+      s_old += (double)(lp - old_lp[r]);
+    }
+    const double t_ref = block_sum(s_ref, sh);
+    const double t_old = block_sum(s_old, sh);
+    const double lo_b = log1p(-(double)clip_eps), hi_b = log1p((double)clip_eps);
+    const double w = exp(fmin(fmax(t_old, lo_b), hi_b));
+    const double delta = (double)log_z[group_idx[i]] + t_ref / n - (double)beta * (double)A;
+    const float ct = (float)(2.0 * w * delta * inv_bn);
+    for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
+      c_c[k] = ct;
+      if (coeff_out) coeff_out[row_map[k]] = ct;
+    }
+    if (threadIdx.x == 0) {
+      seq_loss[i] = (float)(w * delta * delta);
+      gterm[i] = (float)(2.0 * w * delta / (double)B);
+      if (stats) { if (t_old > hi_b) atomicAdd(&stats->n_clip_hi, 1); if (t_old < lo_b) atomicAdd(&stats->n_clip_lo, 1); }
+    }
+  }
+}
+
+// loss = (1/B) sum_i seq_loss_i ;  d_logZ_p = sum over members of gterm  (single workgroup)
+__global__ void finalize_kernel(const float* seq_loss, const float* gterm, const int32_t* group_idx,
+                                const int32_t* seq_len, int B, int P, int objective,
+                                float* loss, float* d_log_z, float* seq_loss_out) {
+  __shared__ double sh[16];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < B; i += blockDim.x) {
+    acc += (double)seq_loss[i];
+    if (seq_loss_out) seq_loss_out[i] = seq_loss[i];
+  }
+  const double tot = block_sum(acc, sh);
+  if (threadIdx.x == 0) *loss = (float)(tot / B);
+  if (d_log_z) {
+    for (int p = threadIdx.x; p < P; p += blockDim.x) {
+      double s = 0.0;
+      if (objective == RL_OBJ_FLOW)
+        for (int i = 0; i < B; ++i) if (group_idx[i] == p && seq_len[i] > 0) s += (double)gterm[i];
+      d_log_z[p] = (float)s;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ transposes (K-contiguous operands)
+// dst[c][r] = src[row_of(r)][c] for r < rows_valid, 0 for rows_valid <= r < ld_dst rows covered by the grid.
+template <class T>
+__global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int cols, const int32_t* row_idx,
+                                 const Ctrl* ctrl, int chunk_start, int dyn_rows,
+                                 T* dst, int64_t ld_dst, int rows_padded) {
+  __shared__ T tile[64][65];
+  int rv = rows;
+  if (dyn_rows) {
+    int left = ctrl->n_real - chunk_start;
+    if (left <= 0) return;
+    rv = left < rows ? left : rows;
+  }
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  if (dyn_rows && r0 >= ((rv + 255) & ~255)) return;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;        // 256 threads: 4 rows per pass
+  for (int k = ty; k < 64; k += 4) {
+    const int r = r0 + k, c = c0 + tx;
+    T v = (T)0.f;
+    if (r < rv && c < cols) {
+      const int64_t sr = row_idx ? (int64_t)row_idx[chunk_start + r] : (int64_t)r;
+      v = src[sr * ld_src + c];
+    }
+    tile[k][tx] = v;
+  }
+  __syncthreads();
+  for (int k = ty; k < 64; k += 4) {
+    const int c = c0 + k, r = r0 + tx;
+    if (c < cols && r < rows_padded) dst[(int64_t)c * ld_dst + r] = tile[tx][k];
+  }
+}
+
+// ------------------------------------------------------------------ host side
+struct Plan {
+  int64_t R; int H, V, B, P; int dtype; size_t esz;
+  int Tc, Vp, tiles_v, n_chunks;
+  bool bwd;
+  size_t off_ctrl, off_seq_len, off_cstart, off_row_map, off_ids_c, off_cpos, off_zy, off_lse_c, off_logp_c,
+      off_c_c, off_adv, off_seq_loss, off_gterm, off_part, off_wt, off_xt, off_ds, off_dst, total;
+};
+
+static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Plan& p) {
+  if (!b) return RL_ERR_NULL;
+  if (b->R < 1 || b->R >= ((int64_t)1 << 31) - (1 << 16) || b->H < 1 || b->V < 1 || b->B < 1 || b->P < 1) return RL_ERR_SHAPE;
+  if (b->dtype != RL_F32 && b->dtype != RL_BF16) return RL_ERR_DTYPE;
+  if (b->dtype == RL_BF16 && (b->H % 8)) return RL_ERR_SHAPE;
+  if (b->dtype == RL_F32 && (b->H % 4)) return RL_ERR_SHAPE;
+  p.R = b->R; p.H = b->H; p.V = b->V; p.B = b->B; p.P = b->P; p.dtype = b->dtype;
+  p.esz = b->dtype == RL_BF16 ? 2 : 4;
+  int tc = (prm && prm->chunk_rows > 0) ? prm->chunk_rows : kDefaultChunkRows;
+  if (prm && prm->chunk_rows < 0) return RL_ERR_SHAPE;
+  const int64_t rp = (b->R + 255) & ~(int64_t)255;
+  tc = (tc + 255) & ~255;
+  if (tc > rp) tc = (int)rp;
+  p.Tc = tc;
+  p.Vp = (b->V + kBM - 1) / kBM * kBM;
+  p.tiles_v = p.Vp / kBM;
+  p.n_chunks = (int)((b->R + tc - 1) / tc);
+  p.bwd = bwd;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+  const size_t Rp = (size_t)rp + 256;
+  p.off_ctrl = take(sizeof(Ctrl));
+  p.off_seq_len = take(sizeof(int32_t) * (size_t)b->B);
+  p.off_cstart = take(sizeof(int32_t) * ((size_t)b->B + 1));
+  p.off_row_map = take(4 * Rp); p.off_ids_c = take(4 * Rp); p.off_cpos = take(4 * Rp);
+  p.off_zy = take(4 * Rp); p.off_lse_c = take(4 * Rp); p.off_logp_c = take(4 * Rp); p.off_c_c = take(4 * Rp);
+  p.off_adv = take(4 * (size_t)b->B); p.off_seq_loss = take(4 * (size_t)b->B); p.off_gterm = take(4 * (size_t)b->B);
+  p.off_part = take(sizeof(float2) * (size_t)p.tiles_v * (size_t)tc);
+  p.off_wt = p.off_xt = p.off_ds = p.off_dst = 0;
+  if (bwd) {
+    p.off_wt = take(p.esz * (size_t)b->H * (size_t)p.Vp);
+    p.off_xt = take(p.esz * (size_t)b->H * (size_t)tc);
+    p.off_ds = take(p.esz * (size_t)tc * (size_t)p.Vp);
+    p.off_dst = take(p.esz * (size_t)p.Vp * (size_t)tc);
+  }
+  p.total = o;
+  return RL_OK;
+}
+
+template <class T, class Epi>
+static void launch_gemm(const T* A, const T* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = gemm_nt_kernel<T, Epi, kBM, kBN, kWavesM, kWavesN>;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmSmem);
+    attr_set = true;
+  }
+  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  kern<<<tiles, kGemmThreads, kGemmSmem, s>>>(A, B, d, epi);
+}
+
+struct Ptrs {
+  Ctrl* ctrl; int32_t *seq_len, *cstart, *row_map, *ids_c, *cpos;
+  float *zy, *lse_c, *logp_c, *c_c, *adv, *seq_loss, *gterm; float2* part;
+  void *wt, *xt, *ds, *dst;
+};
+
+static Ptrs carve(void* ws, const Plan& p) {
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  Ptrs q;
+  q.ctrl = (Ctrl*)(w + p.off_ctrl); q.seq_len = (int32_t*)(w + p.off_seq_len); q.cstart = (int32_t*)(w + p.off_cstart);
+  q.row_map = (int32_t*)(w + p.off_row_map); q.ids_c = (int32_t*)(w + p.off_ids_c); q.cpos = (int32_t*)(w + p.off_cpos);
+  q.zy = (float*)(w + p.off_zy); q.lse_c = (float*)(w + p.off_lse_c); q.logp_c = (float*)(w + p.off_logp_c);
+  q.c_c = (float*)(w + p.off_c_c); q.adv = (float*)(w + p.off_adv); q.seq_loss = (float*)(w + p.off_seq_loss);
+  q.gterm = (float*)(w + p.off_gterm); q.part = (float2*)(w + p.off_part);
+  q.wt = w + p.off_wt; q.xt = w + p.off_xt; q.ds = w + p.off_ds; q.dst = w + p.off_dst;
+  return q;
+}
+
+// prep: counts, scan, compaction; zero the per-row outputs so masked rows read 0
+static void run_prep(const rl_batch* b, const Plan& p, const Ptrs& q, int32_t* seq_len_out, rl_stats* stats,
+                     const int32_t* group_idx, float* logp_out, float* lse_out, float* coeff_out, hipStream_t s) {
+  ProfScope ps(RL_PROF_PREP, s);
+  if (stats) fill<int32_t>(reinterpret_cast<int32_t*>(stats), sizeof(rl_stats) / 4, 0, s);
+  fill<int32_t>(q.cpos, p.R, -1, s);
+  fill<float>(logp_out, p.R, 0.f, s); fill<float>(lse_out, p.R, 0.f, s); fill<float>(coeff_out, p.R, 0.f, s);
+  seq_count_kernel<<<p.B, 256, 0, s>>>(b->mask, b->token_ids, b->cu_seqlens, group_idx, p.R, p.V, p.P, q.seq_len, stats);
+  seq_scan_kernel<<<1, 1024, 0, s>>>(q.seq_len, p.B, q.cstart, q.ctrl, stats);
+  compact_kernel<<<p.B, 1024, 0, s>>>(b->mask, b->token_ids, b->cu_seqlens, q.seq_len, q.cstart, p.V, q.row_map, q.ids_c, q.cpos);
+  if (seq_len_out) (void)hipMemcpyAsync(seq_len_out, q.seq_len, 4 * (size_t)p.B, hipMemcpyDeviceToDevice, s);
+}
+
+template <class T>
+static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* logp_out, float* lse_out, hipStream_t s) {
+  const T* X = static_cast<const T*>(b->hidden);
+  const T* W = static_cast<const T*>(b->weight);
+  for (int ch = 0; ch < p.n_chunks; ++ch) {
+    const int c0 = ch * p.Tc;
+    GemmDims d{};
+    d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
+    d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = 8;
+    EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V};
+    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm<T>(W, X, d, e, s); }
+    ProfScope ps(RL_PROF_COMBINE, s);
+    lse_combine_kernel<<<(p.Tc + 255) / 256, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
+                                                        q.lse_c, q.logp_c, lse_out, logp_out);
+  }
+}
+
+template <class T>
+static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* d_hidden, float* d_weight, hipStream_t s) {
+  const T* X = static_cast<const T*>(b->hidden);
+  const T* W = static_cast<const T*>(b->weight);
+  T* WT = static_cast<T*>(q.wt); T* XT = static_cast<T*>(q.xt);
+  T* dS = static_cast<T*>(q.ds); T* dST = static_cast<T*>(q.dst);
+  T* dX = static_cast<T*>(d_hidden);
+  // masked rows of dX are zero; rows that count are written by the dX epilogue
+  {
+    ProfScope ps(RL_PROF_TRANSPOSE, s);
+    const int rows_per_block = 4;
+    zero_masked_rows_kernel<T><<<(unsigned)((p.R + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(q.cpos, dX, p.R, p.H);
+  }
+  // W^T [H][Vp] with zero padding columns, once per call
+  {
+    ProfScope ps(RL_PROF_TRANSPOSE, s);
+    dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
+    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, WT, p.Vp, p.Vp);
+  }
+  for (int ch = 0; ch < p.n_chunks; ++ch) {
+    const int c0 = ch * p.Tc;
+    {  // X^T chunk [H][Tc], gathered through row_map, zero beyond the valid rows
+      ProfScope ps(RL_PROF_TRANSPOSE, s);
+      dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
+      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, XT, p.Tc, p.Tc);
+    }
+    {  // recompute logits, form dS and dS^T
+      GemmDims d{};
+      d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
+      d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = 8;
+      EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V};
+      ProfScope ps(RL_PROF_GEMM_DS, s);
+      launch_gemm<T>(W, X, d, e, s);
+    }
+    {  // dX = dS W  : A = dS [Tc][Vp], B = W^T [H][Vp]
+      GemmDims d{};
+      d.M = p.Tc; d.N = p.H; d.K = p.Vp; d.lda = p.Vp; d.ldb = p.Vp;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = 8;
+      EpiDX<T> e{q.row_map, dX, p.H, p.H};
+      ProfScope ps(RL_PROF_GEMM_DX, s);
+      launch_gemm<T>(dS, WT, d, e, s);
+    }
+    {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
+      GemmDims d{};
+      d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = 8;
+      EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
+      ProfScope ps(RL_PROF_GEMM_DW, s);
+      launch_gemm<T>(dST, XT, d, e, s);
+    }
+  }
+}
+
+static rl_status check_ws(void* ws, size_t bytes, const Plan& p) {
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || bytes < p.total) return RL_ERR_WORKSPACE;
+  return RL_OK;
+}
+
+}  // namespace rlk
+
+using namespace rlk;
+
+extern "C" {
+
+const char* rl_status_string(int32_t s) {
+  switch (s) {
+    case RL_OK: return "ok";
+    case RL_ERR_NULL: return "a required pointer is NULL";
+    case RL_ERR_SHAPE: return "a size is non-positive, too large or misaligned";
+    case RL_ERR_DTYPE: return "unknown dtype";
+    case RL_ERR_RANGE: return "objective or a coefficient is out of range";
+    case RL_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
+    case RL_ERR_HIP: return "a HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+void rl_profile_enable(int32_t on) { g_prof.on = (on != 0); }
+
+rl_status rl_profile_read(rl_profile* out) {
+  if (!out) return RL_ERR_NULL;
+  memset(out, 0, sizeof(*out));
+  rl_status st = RL_OK;
+  for (const ProfRec& r : g_prof.recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) st = RL_ERR_HIP;
+    else if (r.cls >= 0 && r.cls < RL_PROF_CLASSES) { out->ms[r.cls] += (double)ms; out->launches[r.cls] += 1; }
+    g_prof.pool.push_back({r.a, r.b});
+  }
+  g_prof.recs.clear();
+  return st;
+}
+
+int32_t rl_version(void) { return 100; }
+int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
+
+rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params, int32_t want_backward, size_t* bytes) {
+  if (!batch || !bytes) return RL_ERR_NULL;
+  Plan p;
+  rl_status st = make_plan(batch, params, want_backward != 0, p);
+  if (st != RL_OK) return st;
+  *bytes = p.total;
+  return RL_OK;
+}
+
+rl_status rl_token_logprob(const rl_batch* b, float* logprob, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  if (!b) return RL_ERR_NULL;
+  if (!b->hidden || !b->weight || !b->token_ids || !b->mask || !b->cu_seqlens) return RL_ERR_NULL;
+  if (!logprob && !lse) return RL_ERR_NULL;
+  Plan p;
+  rl_status st = make_plan(b, nullptr, false, p);
+  if (st != RL_OK) return st;
+  st = check_ws(ws, ws_bytes, p);
+  if (st != RL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  Ptrs q = carve(ws, p);
+  run_prep(b, p, q, nullptr, nullptr, nullptr, logprob, lse, nullptr, s);
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, logprob, lse, s);
+  else run_forward<float>(b, p, q, logprob, lse, s);
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_t objective, const rl_outputs* out,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  if (!b || !prm || !out) return RL_ERR_NULL;
+  if (!b->hidden || !b->weight || !b->token_ids || !b->mask || !b->cu_seqlens || !b->group_idx || !b->rewards ||
+      !b->old_logprob || !b->ref_logprob || !out->loss)
+    return RL_ERR_NULL;
+  if (objective != RL_OBJ_GRPO && objective != RL_OBJ_FLOW) return RL_ERR_RANGE;
+  if (objective == RL_OBJ_FLOW && !b->log_z) return RL_ERR_NULL;
+  if (!(prm->clip_eps > 0.f && prm->clip_eps < 1.f)) return RL_ERR_RANGE;
+  if (prm->adv_std_ddof != 0 && prm->adv_std_ddof != 1) return RL_ERR_RANGE;
+  if (!(prm->adv_eps >= 0.f)) return RL_ERR_RANGE;
+  const bool bwd = out->d_hidden || out->d_weight;
+  if (bwd && (!out->d_hidden || !out->d_weight)) return RL_ERR_NULL;
+  Plan p;
+  rl_status st = make_plan(b, prm, bwd, p);
+  if (st != RL_OK) return st;
+  st = check_ws(ws, ws_bytes, p);
+  if (st != RL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  Ptrs q = carve(ws, p);
+
+  run_prep(b, p, q, out->seq_len, out->stats, b->group_idx, out->logprob, out->lse, out->coeff, s);
+  {
+  ProfScope ps(RL_PROF_LOSS, s);
+  fill<float>(q.adv, p.B, 0.f, s);
+  advantage_kernel<<<(p.P + 127) / 128, 128, 0, s>>>(b->rewards, b->group_idx, p.B, p.P, prm->adv_eps, prm->adv_std_ddof, q.adv);
+  if (out->advantages) (void)hipMemcpyAsync(out->advantages, q.adv, 4 * (size_t)p.B, hipMemcpyDeviceToDevice, s);
+  }
+
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, out->logprob, out->lse, s);
+  else run_forward<float>(b, p, q, out->logprob, out->lse, s);
+
+  {
+  ProfScope ps(RL_PROF_LOSS, s);
+  seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
+                                     b->group_idx, b->log_z, p.B, prm->clip_eps, prm->kl_coef, prm->beta,
+                                     q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats);
+  finalize_kernel<<<1, 1024, 0, s>>>(q.seq_loss, q.gterm, b->group_idx, q.seq_len, p.B, p.P, objective,
+                                    out->loss, out->d_log_z, out->seq_loss);
+  }
+  if (bwd) {
+    if (p.dtype == RL_BF16) run_backward<bf16_t>(b, p, q, out->d_hidden, out->d_weight, s);
+    else run_backward<float>(b, p, q, out->d_hidden, out->d_weight, s);
+  }
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+}  // extern "C"

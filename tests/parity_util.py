@@ -1,0 +1,105 @@
+"""Shared helpers of the GPU parity tests: move one seeded batch to both sides and compare.
+
+The HIP path and the oracle read the same stored bits (bf16 tensors are handed to the oracle
+as their 16-bit patterns, which it widens exactly)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import policy_oracle as orc
+from paper_2603_16435_amd import binding
+
+OBJ = {"grpo": (orc.GRPO, binding.RL_OBJ_GRPO), "flow": (orc.FLOW, binding.RL_OBJ_FLOW)}
+
+
+def np_bits(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy()
+    return t.numpy()
+
+
+def oracle_inputs(b, rows=None):
+    """numpy views of a RolloutBatch for the oracle (optionally only the given rows of the row tensors)."""
+    sel = (lambda t: t) if rows is None else (lambda t: t[rows])
+    return dict(hidden=np_bits(sel(b.hidden)), weight=np_bits(b.weight), token_ids=np_bits(sel(b.token_ids)),
+                mask=np_bits(sel(b.mask)), old_logprob=np_bits(sel(b.old_logprob)),
+                ref_logprob=np_bits(sel(b.ref_logprob)))
+
+
+def run_oracle(b, objective: str, want_dw=True, **over):
+    c = b.cfg
+    kw = dict(clip_eps=c.clip_eps, kl_coef=c.kl_coef, beta=c.beta, adv_eps=c.adv_eps, adv_std_ddof=c.adv_std_ddof)
+    kw.update(over)
+    inp = oracle_inputs(b)
+    return orc.policy_loss_fwd_bwd(OBJ[objective][0], cu_seqlens=np_bits(b.cu_seqlens), group_idx=np_bits(b.group_idx),
+                                   rewards=np_bits(b.rewards), log_z=np_bits(b.log_z), P=c.P, want_dw=want_dw,
+                                   **inp, **kw)
+
+
+def run_gpu(b, objective: str, chunk_rows=0, backward=True, **over):
+    c = b.cfg
+    kw = dict(clip_eps=c.clip_eps, kl_coef=c.kl_coef, beta=c.beta, adv_eps=c.adv_eps, adv_std_ddof=c.adv_std_ddof)
+    kw.update(over)
+    res = binding.rl_policy_loss_fwd_bwd(OBJ[objective][1], b.hidden, b.weight, b.token_ids, b.mask, b.cu_seqlens,
+                                         b.group_idx, b.rewards, b.old_logprob, b.ref_logprob, b.log_z, P=c.P,
+                                         chunk_rows=chunk_rows, backward=backward, **kw)
+    torch.cuda.synchronize()
+    return res
+
+
+def f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def loss_rel_err(gpu_loss: float, ref: dict) -> float:
+    """|L_gpu - L_ref| / max(|L_ref|, mean_i |seq_loss_i|): the GRPO loss is ~0 by construction
+    (zero-mean advantages), so the error is measured against the scale of its terms."""
+    scale = max(abs(ref["loss"]), float(np.abs(ref["seq_loss"]).mean()), 1e-30)
+    return abs(gpu_loss - ref["loss"]) / scale
+
+
+def compare_all(b, res, ref, *, loss_tol, logp_atol, grad_tol, check_dw=True):
+    """Element-by-element comparison of every output; returns a dict of the error figures."""
+    m = np_bits(b.mask).astype(bool)
+    err = {}
+    # integer / index work: exact
+    np.testing.assert_array_equal(res.seq_len.cpu().numpy(), ref["seq_len"])
+    st = res.stats_dict()
+    assert st["n_tokens"] == int(ref["seq_len"].sum())
+    assert st["n_bad_token"] == 0 and st["n_bad_group"] == 0 and st["n_bad_seq"] == 0
+    lp = f64(res.logprob); lse = f64(res.lse); coeff = f64(res.coeff)
+    assert np.all(lp[~m] == 0) and np.all(lse[~m] == 0) and np.all(coeff[~m] == 0)
+    # floats
+    err["logp"] = float(np.abs(lp - ref["logprob"]).max())
+    err["lse"] = float(np.abs(lse - ref["lse"]).max())
+    assert err["logp"] <= logp_atol and err["lse"] <= logp_atol, err
+    np.testing.assert_allclose(f64(res.advantages), ref["advantages"], atol=2e-6, rtol=1e-6)
+    err["loss"] = loss_rel_err(float(res.loss.item()), ref)
+    sl_scale = max(float(np.abs(ref["seq_loss"]).max()), 1e-30)
+    err["seq_loss"] = float(np.abs(f64(res.seq_loss) - ref["seq_loss"]).max()) / sl_scale
+    # allowed: the stated relative tolerance, plus the first-order effect of logp being an f32
+    # output (|dL| <= sum_t |c_t| * ulp): it only matters when the loss itself is tiny
+    # (e.g. a lone KL term ~ d^2/2), where a relative bound alone is ill-conditioned.
+    slack = float(np.abs(ref["c"]).sum()) * 1e-6
+    scale = max(abs(ref["loss"]), float(np.abs(ref["seq_loss"]).mean()), 1e-30)
+    assert abs(float(res.loss.item()) - ref["loss"]) <= loss_tol * scale + slack, err
+    assert float(np.abs(f64(res.seq_loss) - ref["seq_loss"]).max()) <= loss_tol * sl_scale + slack * len(ref["seq_loss"]), err
+    c_scale = max(float(np.abs(ref["c"]).max()), 1e-30)
+    err["coeff"] = float(np.abs(coeff - ref["c"]).max()) / c_scale
+    assert err["coeff"] <= max(loss_tol, 1e-4), err
+    np.testing.assert_allclose(f64(res.d_log_z), ref["d_log_z"], atol=loss_tol * max(1.0, float(np.abs(ref["d_log_z"]).max())))
+    if res.d_hidden is not None:
+        dX = f64(res.d_hidden)
+        assert np.all(dX[~m] == 0)                      # masked rows: exactly zero
+        nz_rows = np.abs(ref["d_hidden"]).max(1) > 0
+        assert np.all(np.abs(dX).max(1)[nz_rows] > 0)   # same set of rows carries gradient
+        gx = max(float(np.abs(ref["d_hidden"]).max()), 1e-30)
+        err["dX"] = float(np.abs(dX - ref["d_hidden"]).max()) / gx
+        assert err["dX"] <= grad_tol, err
+        if check_dw:
+            gw = max(float(np.abs(ref["d_weight"]).max()), 1e-30)
+            err["dW"] = float(np.abs(f64(res.d_weight) - ref["d_weight"]).max()) / gw
+            assert err["dW"] <= grad_tol, err
+    return err

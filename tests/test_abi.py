@@ -1,0 +1,104 @@
+"""The C-ABI library: loads, exports every symbol the header declares, and rejects bad host
+arguments before anything is launched (no GPU needed: none of these calls reaches a kernel)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_16435_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(rl_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_16435_amd import build
+        build.build(verbose=False)
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"rl_workspace_bytes", "rl_token_logprob", "rl_policy_loss_fwd_bwd", "rl_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert lib.rl_version() >= 100
+    assert lib.rl_default_chunk_rows() % 256 == 0
+
+
+def _batch(**over):
+    b = binding.rl_batch()
+    b.R, b.H, b.V, b.B, b.P, b.dtype = 1000, 64, 512, 4, 2, binding.RL_BF16
+    for k, v in over.items():
+        setattr(b, k, v)
+    return b
+
+
+def test_workspace_query_and_shape_errors(lib):
+    n = C.c_size_t(0)
+    assert lib.rl_workspace_bytes(C.byref(_batch()), None, 1, C.byref(n)) == 0
+    fwd = C.c_size_t(0)
+    assert lib.rl_workspace_bytes(C.byref(_batch()), None, 0, C.byref(fwd)) == 0
+    assert 0 < fwd.value < n.value and n.value % 256 == 0
+    # chunk_rows grows the staged dS buffers
+    small, big = C.c_size_t(0), C.c_size_t(0)
+    b = _batch(R=100000)
+    lib.rl_workspace_bytes(C.byref(b), C.byref(binding.make_params(chunk_rows=256)), 1, C.byref(small))
+    lib.rl_workspace_bytes(C.byref(b), C.byref(binding.make_params(chunk_rows=4096)), 1, C.byref(big))
+    assert small.value < big.value
+    for bad in (dict(R=0), dict(H=0), dict(V=0), dict(B=0), dict(P=0), dict(H=60), dict(R=1 << 31)):
+        assert lib.rl_workspace_bytes(C.byref(_batch(**bad)), None, 1, C.byref(n)) == 2, bad
+    assert lib.rl_workspace_bytes(C.byref(_batch(dtype=7)), None, 1, C.byref(n)) == 3
+    assert lib.rl_workspace_bytes(None, None, 1, C.byref(n)) == 1
+    assert lib.rl_workspace_bytes(C.byref(_batch()), None, 1, None) == 1
+    assert lib.rl_workspace_bytes(C.byref(_batch(dtype=binding.RL_F32, H=60)), None, 1, C.byref(n)) == 0
+
+
+def test_null_and_range_errors_are_rejected_on_the_host(lib):
+    b = _batch()
+    prm = binding.make_params()
+    out = binding.rl_outputs()
+    # required pointers missing
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), None, 0, None) == 1
+    assert lib.rl_token_logprob(C.byref(b), None, None, None, 0, None) == 1
+    # fake non-null pointers: validation still stops before any launch
+    fake = 0x1000
+    for f in ("hidden", "weight", "token_ids", "mask", "cu_seqlens", "group_idx", "rewards", "old_logprob", "ref_logprob"):
+        setattr(b, f, fake)
+    out.loss = fake
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 5, C.byref(out), None, 0, None) == 4      # objective
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 1, C.byref(out), None, 0, None) == 1      # FLOW needs log_z
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(clip_eps=1.5)), 0, C.byref(out), None, 0, None) == 4
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(adv_std_ddof=2)), 0, C.byref(out), None, 0, None) == 4
+    out.d_hidden = fake                                                                                   # d_weight missing
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), None, 0, None) == 1
+    out.d_weight = fake
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), None, 0, None) == 5      # no workspace
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), 0x1001, 1 << 40, None) == 5  # misaligned
+    assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), 0x1000, 16, None) == 5   # too small
+    assert lib.rl_token_logprob(C.byref(b), fake, None, 0x1000, 16, None) == 5
+    assert b"workspace" in lib.rl_status_string(5)
+
+
+def test_product_path_has_no_oracle_dependency():
+    """The package must not import the oracle (it is test infrastructure)."""
+    pkg = os.path.join(ROOT, "paper_2603_16435_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.replace("CPU oracle", "").lower() or fn == "synth.py", (dirpath, fn)
