@@ -18,6 +18,7 @@ template <> __device__ inline float fast_exp<float>(float x) { return expf(x); }
 //      z_t[y_t] is written by the single lane that holds vocab row y_t of token t.
 template <class T>
 struct EpiFwd {
+  __device__ void keep_alive() const { zy_c[0] = 0.f; }
   const int* ids_c;     // [chunk-global compact row] sampled token
   float* zy_c;          // [compact row] target logit
   float2* part;         // [tiles_m(V)][ldp] partial (max, sumexp) per token
@@ -25,7 +26,7 @@ struct EpiFwd {
   int V;
 
   template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
-  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
     float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
     const float NEG = -__builtin_inff();
 #pragma unroll
@@ -95,13 +96,14 @@ template <> struct Pack4<float> {
 //      dW = dS^T X), so that both later contractions have K contiguous.
 template <class T>
 struct EpiDS {
+  __device__ void keep_alive() const { dS[0] = (T)0.f; }
   const int* ids_c; const float* lse_c; const float* c_c;
   T* dS;  int64_t ld_ds;    // [chunk rows][Vp]
   T* dST; int64_t ld_dst;   // [Vp][chunk rows]
   int V;
 
   template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
-  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
 #pragma unroll
     for (int bj = 0; bj < NB; ++bj) {
       const int n = c.n0 + acc_col(bj, c.lane);
@@ -133,11 +135,12 @@ struct EpiDS {
 // ---- backward, stage 2: dX tile -> rows scattered back to their original positions
 template <class T>
 struct EpiDX {
+  __device__ void keep_alive() const { dX[0] = (T)0.f; }
   const int* row_map;   // compact row -> original row
   T* dX; int64_t ldx; int H;
 
   template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
-  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
@@ -156,10 +159,11 @@ struct EpiDX {
 
 // ---- backward, stage 3: dW tile, f32, overwritten by the first chunk and accumulated after
 struct EpiDW {
+  __device__ void keep_alive() const { dW[0] = 0.f; }
   float* dW; int64_t ldw; int V, H; int accumulate;
 
   template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
-  __device__ void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
+  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll

@@ -1,4 +1,4 @@
-// gemm_nt.h - the one contraction main loop of the library (gfx950 / CDNA4).
+// gemm_nt.h - the contraction main loops of the library (gfx950 / CDNA4).
 //
 //   C[m,n] = sum_k A[m,k] * B[n,k]        A: [M,K] row-major, B: [N,K] row-major ("NT")
 //
@@ -6,13 +6,25 @@
 // so that one MFMA main loop serves the forward logits, the recomputed logits, dX and dW;
 // what differs is the epilogue functor that consumes the accumulators in registers.
 //
-// Tiling: a workgroup of WAVES_M x WAVES_N wavefronts (64 lanes each) owns a BM x BN tile of
-// C and walks K in slabs of 128 bytes per row (64 bf16 or 32 f32).  Slabs are staged in LDS
-// (double-buffered; global loads for slab k+1 are in flight while slab k feeds the MFMAs).
+// Two kernels share tile order, LDS layout and epilogues:
+//  * gemm_nt_bf16_kernel  - the hot one (bf16, K % 64 == 0).  256x256 tile, four wavefronts of
+//    128x128 each (256 accumulator registers per lane live in AGPRs, one wavefront per SIMD),
+//    K walked in slabs of 64.  Slabs go from global memory straight into LDS
+//    (global_load ... lds, 16 bytes per lane) into two static 64 KiB stages; the loads of a slab
+//    are spread over three k-steps so that no burst blocks the MFMA issue, fragments of k-step
+//    s+1 are read from LDS while k-step s feeds the MFMAs, and the last k-step of a slab runs
+//    after the workgroup barrier so that it hides the first fragment reads of the next slab.
+//    The interleaving is pinned with sched_group_barrier.  A light software prefetch (one 4-byte
+//    load per 128-byte line, a few slabs ahead, shared between the workgroups of an XCD) pulls
+//    the next panels into that XCD's L2.
+//  * gemm_nt_kernel       - generic fallback (f32 inputs, or K not a multiple of 64): eight
+//    wavefronts of 128x64, register-staged loads with a K-tail predicate.
+//
 // LDS rows are 128 B = eight 16-byte chunks; chunk c of row r sits at slot c ^ ((r>>1)&7),
 // which spreads both the 16-byte row-wise stores and the column-wise fragment loads over all
-// 64 banks.  MFMA shape is 32x32 (x16 for bf16, x2 for f32); both have the same accumulator
-// layout: lane l, register i hold  row = 8*(i/4) + 4*(l/32) + i%4,  col = l%32.
+// 64 banks (measured: zero bank conflicts).  MFMA shape is 32x32 (x16 for bf16, x2 for f32);
+// both have the same accumulator layout: lane l, register i hold
+// row = 8*(i/4) + 4*(l/32) + i%4,  col = l%32.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -195,6 +207,179 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
   c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
   c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
   epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N>(acc, c, smem, d);
+}
+
+// ------------------------------------------------------------------ bf16 hot kernel
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+__device__ inline void load16_to_lds(const void* g, void* l) {   // 64 lanes x 16 B -> 1 KiB of LDS at l
+  __builtin_amdgcn_global_load_lds((glb_ptr_t)g, (lds_ptr_t)l, 16, 0, 0);
+}
+
+template <class Epi, int PFD>   // PFD: L2 prefetch distance in slabs (0 = none)
+__global__ __launch_bounds__(256)
+void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, Epi epi) {
+  constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2;
+  constexpr int WM = 128, WN = 128, MB = 4, NB = 4;
+  constexpr int A_BYTES = BM * kSlabBytes, B_BYTES = BN * kSlabBytes, STAGE = A_BYTES + B_BYTES;
+  // two separate objects: the compiler can then tell the stage being filled by the DMA loads from the
+  // stage the fragments are read from, and does not serialise them with a vmcnt(0)
+  __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
+  __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
+
+  int M = d.M, N = d.N, K = d.K;
+  if (d.dyn) {
+    const int left = *d.n_real - d.chunk_start;
+    if (left <= 0) {
+      if (d.dyn == 3 && d.chunk_start == 0) K = 0; else return;
+    } else if (d.dyn == 1) M = left < M ? left : M;
+    else if (d.dyn == 2) N = left < N ? left : N;
+    else { const int k = (left + 255) & ~255; K = k < K ? k : K; }
+  }
+  const int nk = K / BK;
+  const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+  int tm, tn;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, d.group_m, tm, tn);
+  if (tm * BM >= M || tn * BN >= N) return;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: LDS addresses stay scalar
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- slab staging.  Wavefront w fills rows [64w, 64w+64) of A and of B: eight loads of eight
+  // rows each.  A load writes lane l's 16 bytes to LDS offset 16*l of its 1 KiB target, i.e. row
+  // l/8, slot l%8; the swizzle is therefore applied on the global side (which chunk a lane fetches).
+  const bf16_t* ap[8];
+  const bf16_t* bp[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int lr = wave * 64 + j * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((lr >> 1) & 7);
+    int r = tm * BM + lr; r = r < M ? r : M - 1;
+    if (d.a_rows) r = d.a_rows[r];
+    ap[j] = A + (int64_t)r * d.lda + c * 8;
+    r = tn * BN + lr; r = r < N ? r : N - 1;
+    if (d.b_rows) r = d.b_rows[r];
+    bp[j] = B + (int64_t)r * d.ldb + c * 8;
+  }
+  // loads j in [lo,hi) of the 16 per slab (0..7 = A rows, 8..15 = B rows)
+  auto issue = [&](int k0, unsigned char* stage, int lo, int hi) __attribute__((always_inline)) {
+    unsigned char* as = stage + wave * 64 * kSlabBytes;
+    unsigned char* bs = as + A_BYTES;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (j < lo || j >= hi) continue;
+      if (j < 8) load16_to_lds(ap[j] + k0, as + j * 8 * kSlabBytes);
+      else load16_to_lds(bp[j - 8] + k0, bs + (j - 8) * 8 * kSlabBytes);
+    }
+  };
+
+  // ---- L2 prefetch.  The workgroups resident on one XCD at a time form (about) a block of 8 M-tiles
+  // by 4 N-tiles that walks K in lock-step.  Wavefront 0 touches one quarter of the A panel rows,
+  // wavefront 1 one eighth of the B panel rows, PFD slabs ahead, one 4-byte load per 128-byte line:
+  // between them the block's workgroups cover every line once.  Wavefronts 2 and 3 execute the same
+  // instruction on one fixed line (no divergent control flow around the accumulators).
+  const unsigned char* pf_ptr;
+  int pf_stride = BK * 2;
+  if (wave == 0) {
+    int r = tm * BM + 64 * (tn & 3) + lane; r = r < M ? r : M - 1;
+    if (d.a_rows) r = d.a_rows[r];
+    pf_ptr = reinterpret_cast<const unsigned char*>(A + (int64_t)r * d.lda);
+  } else if (wave == 1) {
+    int r = tn * BN + 32 * (tm & 7) + (lane & 31); r = r < N ? r : N - 1;
+    if (d.b_rows) r = d.b_rows[r];
+    pf_ptr = reinterpret_cast<const unsigned char*>(B + (int64_t)r * d.ldb);
+  } else {
+    pf_ptr = reinterpret_cast<const unsigned char*>(A);
+    pf_stride = 0;
+  }
+  unsigned pf0 = 0, pf1 = 0, pf_sink = 0;
+  auto prefetch = [&](unsigned& slot, int kt) __attribute__((always_inline)) {
+    if (PFD > 0) {
+      pf_sink ^= slot;                                   // fetched two slabs ago: long since back
+      const int k = kt + PFD < nk ? kt + PFD : nk - 1;
+      slot = *reinterpret_cast<const unsigned*>(pf_ptr + (int64_t)k * pf_stride);
+    }
+  };
+
+  floatx16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // ---- fragments: two register sets, k-step s+1 is fetched while k-step s is multiplied
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const int arow = (wm * WM + frow) * kSlabBytes, brow = A_BYTES + (wn * WN + frow) * kSlabBytes;
+  const int swz = (frow >> 1) & 7;                 // the other row blocks are 32 rows apart: same swizzle
+  uint4 fa[2][MB], fb[2][NB];
+  auto fetch = [&](int set, const unsigned char* stage, int s) __attribute__((always_inline)) {
+    const int slot = ((s * 2 + fhalf) ^ swz) << 4;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) fa[set][i] = *reinterpret_cast<const uint4*>(stage + arow + i * 32 * kSlabBytes + slot);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) fb[set][j] = *reinterpret_cast<const uint4*>(stage + brow + j * 32 * kSlabBytes + slot);
+  };
+  auto mma = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) mma_step<bf16_t>(fa[set][i], fb[set][j], acc[i][j]);
+  };
+  // one k-step = 16 MFMA: the first eight each followed by one fragment read, the next nvmem each
+  // followed by one slab load; a full fence keeps the steps apart
+  auto pin = [&](int nvmem) __attribute__((always_inline)) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (q < nvmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto kof = [&](int k) __attribute__((always_inline)) { return (k < nk ? k : nk - 1) * BK; };   // past the end: harmless re-load
+
+  // slab kt sits in `cur`; on entry fragment set 0 holds its k-step 0 and loads 0..5 of slab kt+1 are
+  // in flight towards `nxt`.
+  auto slab = [&](unsigned char* cur, unsigned char* nxt, int kt, unsigned& pfslot) __attribute__((always_inline)) {
+    prefetch(pfslot, kt);
+    fetch(1, cur, 1); issue(kof(kt + 1), nxt, 6, 11);  mma(0); pin(5);
+    fetch(0, cur, 2); issue(kof(kt + 1), nxt, 11, 16); mma(1); pin(5);
+    fetch(1, cur, 3);                                  mma(0); pin(0);
+    __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0): own loads have landed, own fragment reads are done
+    __syncthreads();                        // ... and so have everybody else's: `nxt` is complete, `cur` is free
+    issue(kof(kt + 2), cur, 0, 6);
+    fetch(0, nxt, 0);                                  mma(1); pin(6);
+  };
+
+  if (nk > 0) {
+    issue(0, stage0, 0, 16);
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
+    __syncthreads();
+    issue(kof(1), stage1, 0, 6);
+    fetch(0, stage0, 0);
+    int kt = 0;
+    for (; kt + 1 < nk; kt += 2) {
+      slab(stage0, stage1, kt, pf0);
+      slab(stage1, stage0, kt + 1, pf1);
+    }
+    if (kt < nk) slab(stage0, stage1, kt, pf0);
+  }
+  __builtin_amdgcn_s_waitcnt(0x0070);       // trailing re-loads must land before the epilogue reuses LDS
+  __syncthreads();
+
+  TileCtx c;
+  c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
+  c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
+  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N>(acc, c, stage0, d);
+  if (PFD > 0 && (pf_sink ^ pf0 ^ pf1) == 0x9E3779B9u && K < 0) epi.keep_alive();   // never true: keeps the prefetch loads
 }
 
 // accumulator coordinates inside a wavefront sub-tile

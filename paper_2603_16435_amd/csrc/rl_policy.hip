@@ -421,16 +421,33 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   return RL_OK;
 }
 
+// The bf16 hot kernel needs whole 64-element slabs and 16-byte aligned rows; anything else (f32
+// inputs, ragged K) takes the generic kernel.  pfd = L2 prefetch distance of the hot kernel.
 template <class T, class Epi>
-static void launch_gemm(const T* A, const T* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
+static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi& epi, int tiles, hipStream_t s) {
   static bool attr_set = false;
   auto kern = gemm_nt_kernel<T, Epi, kBM, kBN, kWavesM, kWavesN>;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmSmem);
     attr_set = true;
   }
-  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
   kern<<<tiles, kGemmThreads, kGemmSmem, s>>>(A, B, d, epi);
+}
+
+template <class Epi>
+static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, const Epi& epi, int pfd, hipStream_t s) {
+  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  const bool fast = (d.K % 64 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
+                    ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
+  if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
+  if (pfd > 0) gemm_nt_bf16_kernel<Epi, 4><<<tiles, 256, 0, s>>>(A, B, d, epi);
+  else gemm_nt_bf16_kernel<Epi, 0><<<tiles, 256, 0, s>>>(A, B, d, epi);
+}
+
+template <class Epi>
+static void launch_gemm(const float* A, const float* B, const GemmDims& d, const Epi& epi, int, hipStream_t s) {
+  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  launch_generic<float, Epi>(A, B, d, epi, tiles, s);
 }
 
 struct Ptrs {
@@ -474,7 +491,7 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
     d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = 8;
     EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V};
-    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm<T>(W, X, d, e, s); }
+    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm(W, X, d, e, 4, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
     lse_combine_kernel<<<(p.Tc + 255) / 256, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
                                                         q.lse_c, q.logp_c, lse_out, logp_out);
@@ -513,7 +530,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = 8;
       EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V};
       ProfScope ps(RL_PROF_GEMM_DS, s);
-      launch_gemm<T>(W, X, d, e, s);
+      launch_gemm(W, X, d, e, 4, s);
     }
     {  // dX = dS W  : A = dS [Tc][Vp], B = W^T [H][Vp]
       GemmDims d{};
@@ -521,7 +538,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = 8;
       EpiDX<T> e{q.row_map, dX, p.H, p.H};
       ProfScope ps(RL_PROF_GEMM_DX, s);
-      launch_gemm<T>(dS, WT, d, e, s);
+      launch_gemm(dS, WT, d, e, 4, s);
     }
     {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
       GemmDims d{};
@@ -529,7 +546,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = 8;
       EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
       ProfScope ps(RL_PROF_GEMM_DW, s);
-      launch_gemm<T>(dST, XT, d, e, s);
+      launch_gemm(dST, XT, d, e, 0, s);
     }
   }
 }
