@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--len-div", type=int, default=1, help="shorten every sequence (debug / profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region, run one plain 1 GiB device copy (reference dispatch for FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
@@ -98,6 +100,14 @@ def main():
     dt = time.perf_counter() - t0
     prof = binding.rl_profile_read()
     binding.rl_profile_enable(False)
+
+    if a.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
 
     T = int(res.stats_dict()["n_tokens"])
     loss = float(res.loss.item())

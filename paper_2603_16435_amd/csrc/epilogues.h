@@ -25,7 +25,7 @@ struct EpiFwd {
   int ldp;              // = chunk rows
   int V;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
     float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
     const float NEG = -__builtin_inff();
@@ -40,18 +40,20 @@ struct EpiFwd {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int m = c.m0 + acc_row(bi, i, c.lane);
-          float v = acc[bi][bj][i];
+          const float v = acc_read<AGPR>(acc[bi][bj], i);
           if (m == y) zy_c[d.chunk_start + n] = v;
-          v = (m < V) ? v : NEG;
-          acc[bi][bj][i] = v;
-          mx = fmaxf(mx, v);
+          mx = fmaxf(mx, (m < V) ? v : NEG);
         }
       const float ms = (mx == NEG) ? 0.f : mx;
       float sm = 0.f;
 #pragma unroll
       for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sm += fast_exp<T>(acc[bi][bj][i] - ms);
+        for (int i = 0; i < 16; ++i) {
+          const int m = c.m0 + acc_row(bi, i, c.lane);
+          const float e = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], i) - ms);
+          sm += (m < V) ? e : 0.f;
+        }
       const float mx2 = __shfl_xor(mx, 32), sm2 = __shfl_xor(sm, 32);
       const float mm = fmaxf(mx, mx2);
       const float mms = (mm == NEG) ? 0.f : mm;
@@ -102,7 +104,7 @@ struct EpiDS {
   T* dST; int64_t ld_dst;   // [Vp][chunk rows]
   int V;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
 #pragma unroll
     for (int bj = 0; bj < NB; ++bj) {
@@ -120,7 +122,7 @@ struct EpiDS {
           float o[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp<T>(acc[bi][bj][q * 4 + e] - lse);
+            const float p = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], q * 4 + e) - lse);
             const float ds = ct * (((m + e) == y ? 1.f : 0.f) - p);
             o[e] = (valid && (m + e) < V) ? ds : 0.f;
           }
@@ -139,7 +141,7 @@ struct EpiDX {
   const int* row_map;   // compact row -> original row
   T* dX; int64_t ldx; int H;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
@@ -151,7 +153,7 @@ struct EpiDX {
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj) {
           const int n = c.n0 + acc_col(bj, c.lane);
-          if (n < H) dX[dst * ldx + n] = (T)acc[bi][bj][i];
+          if (n < H) dX[dst * ldx + n] = (T)acc_read<AGPR>(acc[bi][bj], i);
         }
       }
   }
@@ -162,7 +164,7 @@ struct EpiDW {
   __device__ void keep_alive() const { dW[0] = 0.f; }
   float* dW; int64_t ldw; int V, H; int accumulate;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N>
+  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
@@ -175,7 +177,8 @@ struct EpiDW {
           const int n = c.n0 + acc_col(bj, c.lane);
           if (n < H) {
             float* p = dW + (int64_t)m * ldw + n;
-            *p = accumulate ? (*p + acc[bi][bj][i]) : acc[bi][bj][i];
+            const float v = acc_read<AGPR>(acc[bi][bj], i);
+            *p = accumulate ? (*p + v) : v;
           }
         }
       }

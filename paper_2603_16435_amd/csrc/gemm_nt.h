@@ -7,7 +7,7 @@
 // what differs is the epilogue functor that consumes the accumulators in registers.
 //
 // Two kernels share tile order, LDS layout and epilogues:
-//  * gemm_nt_bf16_kernel  - the hot one (bf16, K % 64 == 0).  256x256 tile, four wavefronts of
+//  * gemm_nt_bf16_kernel  - the hot one (bf16, K % 128 == 0).  256x256 tile, four wavefronts of
 //    128x128 each (256 accumulator registers per lane live in AGPRs, one wavefront per SIMD),
 //    K walked in slabs of 64.  Slabs go from global memory straight into LDS
 //    (global_load ... lds, 16 bytes per lane) into two static 64 KiB stages; the loads of a slab
@@ -17,7 +17,7 @@
 //    The interleaving is pinned with sched_group_barrier.  A light software prefetch (one 4-byte
 //    load per 128-byte line, a few slabs ahead, shared between the workgroups of an XCD) pulls
 //    the next panels into that XCD's L2.
-//  * gemm_nt_kernel       - generic fallback (f32 inputs, or K not a multiple of 64): eight
+//  * gemm_nt_kernel       - generic fallback (f32 inputs, or K not a multiple of 128): eight
 //    wavefronts of 128x64, register-staged loads with a K-tail predicate.
 //
 // LDS rows are 128 B = eight 16-byte chunks; chunk c of row r sits at slot c ^ ((r>>1)&7),
@@ -206,7 +206,7 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
   TileCtx c;
   c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
   c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
-  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N>(acc, c, smem, d);
+  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N, false>(acc, c, smem, d);
 }
 
 // ------------------------------------------------------------------ bf16 hot kernel
@@ -365,12 +365,10 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
     __syncthreads();
     issue(kof(1), stage1, 0, 6);
     fetch(0, stage0, 0);
-    int kt = 0;
-    for (; kt + 1 < nk; kt += 2) {
+    for (int kt = 0; kt < nk; kt += 2) {    // nk is even (K % 128 == 0 is a launch condition)
       slab(stage0, stage1, kt, pf0);
       slab(stage1, stage0, kt + 1, pf1);
     }
-    if (kt < nk) slab(stage0, stage1, kt, pf0);
   }
   __builtin_amdgcn_s_waitcnt(0x0070);       // trailing re-loads must land before the epilogue reuses LDS
   __syncthreads();
@@ -378,8 +376,24 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
   TileCtx c;
   c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
   c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
-  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N>(acc, c, stage0, d);
+  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N, true>(acc, c, stage0, d);
   if (PFD > 0 && (pf_sink ^ pf0 ^ pf1) == 0x9E3779B9u && K < 0) epi.keep_alive();   // never true: keeps the prefetch loads
+}
+
+// Reading one accumulator element in an epilogue.  In the hot kernel the 256 accumulators of a lane
+// live in AGPRs; left to itself the compiler copies all of them to VGPRs at loop exit and spills
+// most of them to scratch (tens of GB of extra HBM traffic per launch).  Reading each element
+// through an explicit v_accvgpr_read at its point of use keeps them where they are.
+template <bool AGPR>
+__device__ inline float acc_read(const floatx16& v, int i) {
+  if constexpr (AGPR) {
+    float r;
+    const float e = v[i];
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(e));
+    return r;
+  } else {
+    return v[i];
+  }
 }
 
 // accumulator coordinates inside a wavefront sub-tile

@@ -25,7 +25,7 @@
 
 namespace rlk {
 
-constexpr int kDefaultChunkRows = 16384;
+constexpr int kDefaultChunkRows = 32768;
 constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
 constexpr int kGemmThreads = kWavesM * kWavesN * 64;
 constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 KiB per CU
@@ -421,7 +421,7 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   return RL_OK;
 }
 
-// The bf16 hot kernel needs whole 64-element slabs and 16-byte aligned rows; anything else (f32
+// The bf16 hot kernel needs an even number of whole 64-element slabs and 16-byte aligned rows; anything else (f32
 // inputs, ragged K) takes the generic kernel.  pfd = L2 prefetch distance of the hot kernel.
 template <class T, class Epi>
 static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi& epi, int tiles, hipStream_t s) {
@@ -437,7 +437,7 @@ static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi&
 template <class Epi>
 static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, const Epi& epi, int pfd, hipStream_t s) {
   const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
-  const bool fast = (d.K % 64 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
+  const bool fast = (d.K % 128 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
                     ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
   if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
   if (pfd > 0) gemm_nt_bf16_kernel<Epi, 4><<<tiles, 256, 0, s>>>(A, B, d, epi);
