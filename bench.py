@@ -21,6 +21,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
+# HBM-side bytes (L2 <-> fabric; FETCH_SIZE x2.0 + WRITE_SIZE x1.0 after calibration against a plain 1 GiB copy)
+# of one full 32768-row launch of each contraction class on the default workload, from two rocprofv3 --pmc runs
+# whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
+MEASURED_TRAFFIC_7B_CHUNK32768 = {"gemm_fwd": 56.6e9 + 0.2e9, "gemm_ds": 53.2e9 + 20.9e9,
+                                  "gemm_dx": 82.5e9 + 0.2e9, "gemm_dw": 73.3e9 + 2.2e9}
 CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 32, "7b": 512, "long": 2048, "32b": 2048}
 
 
@@ -137,8 +142,13 @@ def main():
                    "chunk_rows": a.chunk_rows or binding.lib().rl_default_chunk_rows()},
         "mfma_frac_6THV": 6.0 * thv / (dt / a.steps) / 1e12 / peak,
         "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
-        "roofline": {"bound": "mfma", "kernel": f"gemm_nt_kernel ({dom})", "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+        "roofline": {"bound": "mfma", "kernel": f"gemm_nt_bf16_kernel ({dom})", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": (MEASURED_TRAFFIC_7B_CHUNK32768[dom]
+                                 if (a.config == "7b" and a.len_div == 1 and a.layout == "padded"
+                                     and (a.chunk_rows or 32768) == 32768) else None),
+                     "traffic_note": "bytes per full 32768-row launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
+                     "flops_per_full_launch": 2.0 * 32768 * cfg.H * cfg.V,
                      "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": int(dom_n)},
         "kernels": kernels,
         "loss": loss,

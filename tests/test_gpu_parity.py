@@ -168,3 +168,76 @@ def test_results_are_bit_reproducible():
     c = run_gpu(b, "grpo", chunk_rows=1024)
     for x, y in ((a.loss, c.loss), (a.logprob, c.logprob), (a.d_hidden, c.d_hidden), (a.d_weight, c.d_weight)):
         assert torch.equal(x, y)
+
+
+# --------------------------------------------------------------------------- full size, bench launch configuration
+@pytest.mark.timeout(900)
+def test_7b_full_size_sampled_sequences():
+    """The 7B-shaped configuration at full size, padded layout, default chunking (what bench.py
+    times).  The oracle cannot do 1.6e14 MACs per pass, so it computes, one by one, everything that
+    belongs to the two shortest sequences (log-probs, lse, sequence loss, per-token coefficient, dX
+    rows - each exact for those rows, given the whole-batch constants B and the advantages, which
+    it also computes) and the rest is checked through exact integer outputs and properties that hold
+    at any size: sum_v dW[v,:] = 0, <dX,X> = <dW,W>, loss = mean(seq_loss), masked rows zero."""
+    b = synth.make_rollouts("7b", "cuda", "padded")
+    c = b.cfg
+    B = b.B
+    lengths = b.lengths.numpy().astype(np.int64)
+    cu = np_bits(b.cu_seqlens).astype(np.int64)
+    pick = np.argsort(lengths, kind="stable")[:2]
+    rows = np.concatenate([np.arange(cu[i], cu[i] + lengths[i]) for i in pick])
+    rows_t = torch.from_numpy(rows).cuda()
+    _say("7b full: R", b.R, "T", b.T, "oracle rows", rows.size, "sequences", pick.tolist())
+    W = np_bits(b.weight)
+    Xs = np_bits(b.hidden[rows_t]); ids_s = np_bits(b.token_ids[rows_t])
+    old_s = np_bits(b.old_logprob[rows_t]); ref_s = np_bits(b.ref_logprob[rows_t])
+    ones = np.ones(rows.size, np.uint8)
+    cu_s = np.concatenate([[0], np.cumsum(lengths[pick])])
+    lp_ref, lse_ref = orc.token_logprob(Xs, W, ids_s, ones)
+    adv_ref = orc.group_advantage(np_bits(b.rewards), np_bits(b.group_idx), c.P, c.adv_eps, c.adv_std_ddof)
+    gidx = np_bits(b.group_idx).astype(np.int64)
+    X64 = None
+    for objective in ("grpo", "flow"):
+        res = run_gpu(b, objective)
+        # exact integer work at full size
+        np.testing.assert_array_equal(res.seq_len.cpu().numpy(), lengths)
+        st = res.stats_dict()
+        assert st["n_tokens"] == b.T and st["n_bad_token"] == 0 and st["n_bad_seq"] == 0
+        np.testing.assert_allclose(f64(res.advantages), adv_ref, atol=2e-6, rtol=1e-6)
+        # the sampled sequences, element by element
+        assert np.abs(f64(res.logprob[rows_t]) - lp_ref).max() <= BF16_TOL["logp_atol"]
+        assert np.abs(f64(res.lse[rows_t]) - lse_ref).max() <= BF16_TOL["logp_atol"]
+        if objective == "grpo":
+            o = orc.grpo_loss(lp_ref, old_s, ref_s, ones, cu_s, adv_ref[pick], c.clip_eps, c.kl_coef)
+        else:
+            o = orc.flow_loss(lp_ref, old_s, ref_s, ones, cu_s, adv_ref[pick], np.arange(2),
+                              np_bits(b.log_z)[gidx[pick]], c.clip_eps, c.beta)
+        c_ref = o["c"] * (2.0 / B)                      # the oracle normalised by its own B = 2
+        sl = f64(res.seq_loss)[pick]
+        assert np.abs(sl - o["seq_loss"]).max() <= BF16_TOL["loss_tol"] * max(np.abs(o["seq_loss"]).max(), 1e-30) + 1e-6
+        assert np.abs(f64(res.coeff[rows_t]) - c_ref).max() <= 1e-2 * np.abs(c_ref).max()
+        dX_ref, _ = orc.lm_head_backward(Xs, W, ids_s, ones, lse_ref, c_ref, want_dw=False)
+        dX = f64(res.d_hidden[rows_t])
+        err = np.abs(dX - dX_ref).max() / np.abs(dX_ref).max()
+        _say("  ", objective, "sampled dX err", err)
+        assert err <= BF16_TOL["grad_tol"]
+        # properties at full size
+        assert abs(float(res.loss.item()) - f64(res.seq_loss).mean()) <= 1e-5 * max(np.abs(f64(res.seq_loss)).mean(), 1e-30)
+        m = b.mask.bool()
+        assert int((res.d_hidden[~m] != 0).sum().item()) == 0
+        assert int((res.logprob[~m] != 0).sum().item()) == 0
+        assert int((res.d_hidden[m].abs().amax(1) > 0).sum().item()) == b.T
+        dW = res.d_weight
+        col = dW.double().sum(0).abs().max().item()
+        assert col <= 1e-3 * dW.abs().max().item() * np.sqrt(dW.shape[0])
+        ip_x = 0.0
+        for s in range(0, b.R, 65536):
+            ip_x += float((res.d_hidden[s:s + 65536].double() * b.hidden[s:s + 65536].double()).sum().item())
+        ip_w = 0.0
+        for s in range(0, c.V, 16384):
+            ip_w += float((dW[s:s + 16384].double() * b.weight[s:s + 16384].double()).sum().item())
+        scale = float(dW.double().abs().sum().item()) * 0.02 * 1e-3 + 1e-30
+        _say("  ", objective, "<dX,X>", ip_x, "<dW,W>", ip_w)
+        assert abs(ip_x - ip_w) <= 2e-2 * max(abs(ip_x), abs(ip_w)) + scale
+        del res
+    del X64
