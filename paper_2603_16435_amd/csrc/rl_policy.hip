@@ -222,25 +222,43 @@ __global__ void advantage_kernel(const float* rewards, const int32_t* group_idx,
 }
 
 // ------------------------------------------------------------------ forward combine
-// Thread per compact row of the chunk: fold the per-vocab-tile partials into lse, logp.
+// Fold the per-vocab-tile partials (max, sumexp) of a chunk into lse, logp.  A workgroup handles 64
+// compact rows x 4 slices of the tile range: one online (rescaling) pass per thread, coalesced
+// along the rows, then the four slices are merged through LDS in a fixed order.
 __global__ void lse_combine_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c,
                                    const int32_t* row_map, const Ctrl* ctrl, int chunk_start, int chunk_rows,
                                    float* lse_c, float* logp_c, float* lse_out, float* logp_out) {
-  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  __shared__ float sm[4][64], ss[4][64];
   int left = ctrl->n_real - chunk_start;
   if (left > chunk_rows) left = chunk_rows;
-  if (n >= left) return;
-  float m = -__builtin_inff();
-  for (int t = 0; t < tiles_v; ++t) m = fmaxf(m, part[(int64_t)t * ldp + n].x);
-  double s = 0.0;
-  for (int t = 0; t < tiles_v; ++t) { const float2 v = part[(int64_t)t * ldp + n]; s += (double)v.y * exp((double)(v.x - m)); }
-  const float lse = (float)((double)m + log(s));
-  const int g = chunk_start + n;
-  const float lp = zy_c[g] - lse;
-  lse_c[g] = lse; logp_c[g] = lp;
-  const int r = row_map[g];
-  if (lse_out) lse_out[r] = lse;
-  if (logp_out) logp_out[r] = lp;
+  if ((int)blockIdx.x * 64 >= left) return;
+  const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + col;
+  const float NEG = -__builtin_inff();
+  float m = NEG, s = 0.f;
+  if (n < left) {
+    for (int t = slice; t < tiles_v; t += 4) {
+      const float2 v = part[(int64_t)t * ldp + n];
+      const float mm = fmaxf(m, v.x);
+      if (mm != NEG) s = s * expf(m - mm) + v.y * expf(v.x - mm);
+      m = mm;
+    }
+  }
+  sm[slice][col] = m; ss[slice][col] = s;
+  __syncthreads();
+  if (slice == 0 && n < left) {
+    float M = sm[0][col];
+    for (int k = 1; k < 4; ++k) M = fmaxf(M, sm[k][col]);
+    double S = 0.0;
+    for (int k = 0; k < 4; ++k) if (sm[k][col] != NEG) S += (double)ss[k][col] * exp((double)(sm[k][col] - M));
+    const float lse = (float)((double)M + log(S));
+    const int g = chunk_start + n;
+    const float lp = zy_c[g] - lse;
+    lse_c[g] = lse; logp_c[g] = lp;
+    const int r = row_map[g];
+    if (lse_out) lse_out[r] = lse;
+    if (logp_out) logp_out[r] = lp;
+  }
 }
 
 // ------------------------------------------------------------------ loss
@@ -493,7 +511,7 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V};
     { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm(W, X, d, e, 4, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
-    lse_combine_kernel<<<(p.Tc + 255) / 256, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
+    lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
                                                         q.lse_c, q.logp_c, lse_out, logp_out);
   }
 }
