@@ -26,7 +26,7 @@ PEAK_F32_TFLOPS = 157.3
 # whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
 MEASURED_TRAFFIC_7B_CHUNK32768 = {"gemm_fwd": 56.6e9 + 0.2e9, "gemm_ds": 53.2e9 + 20.9e9,
                                   "gemm_dx": 82.5e9 + 0.2e9, "gemm_dw": 73.3e9 + 2.2e9}
-CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 32, "7b": 512, "long": 2048, "32b": 2048}
+CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 8, "7b": 160, "long": 640, "32b": 768}   # ~10-30 s of oracle work
 
 
 def cpu_baseline(name: str, objective: str):

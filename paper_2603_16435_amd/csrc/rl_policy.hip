@@ -29,6 +29,11 @@ constexpr int kDefaultChunkRows = 32768;
 constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
 constexpr int kGemmThreads = kWavesM * kWavesN * 64;
 constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 KiB per CU
+// Tile-order band height (M-tiles per band) and L2 prefetch of the hot kernel, per contraction, from
+// sweeps on the 7B-shaped workload at 32768-row chunks: the logits GEMMs like bands of 8 with the
+// prefetch on (261 vs 270 ms per step), dX is best without prefetch (256 vs 280 ms), dW with bands of
+// 4 (270 vs 285 ms); bands of 16 or more lose 5-40 %.
+constexpr int kBandLogits = 8, kPrefetchLogits = 4, kBandDX = 8, kBandDW = 4;
 
 struct Ctrl {            // device control block at the head of the workspace
   int n_real;
@@ -507,9 +512,9 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     const int c0 = ch * p.Tc;
     GemmDims d{};
     d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
-    d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = 8;
+    d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = kBandLogits;
     EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V};
-    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm(W, X, d, e, 4, s); }
+    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm(W, X, d, e, kPrefetchLogits, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
     lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
                                                         q.lse_c, q.logp_c, lse_out, logp_out);
@@ -545,23 +550,23 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
     {  // recompute logits, form dS and dS^T
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
-      d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = 8;
+      d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = kBandLogits;
       EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V};
       ProfScope ps(RL_PROF_GEMM_DS, s);
-      launch_gemm(W, X, d, e, 4, s);
+      launch_gemm(W, X, d, e, kPrefetchLogits, s);
     }
     {  // dX = dS W  : A = dS [Tc][Vp], B = W^T [H][Vp]
       GemmDims d{};
       d.M = p.Tc; d.N = p.H; d.K = p.Vp; d.lda = p.Vp; d.ldb = p.Vp;
-      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = 8;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = kBandDX;
       EpiDX<T> e{q.row_map, dX, p.H, p.H};
       ProfScope ps(RL_PROF_GEMM_DX, s);
-      launch_gemm(dS, WT, d, e, 4, s);
+      launch_gemm(dS, WT, d, e, 0, s);
     }
     {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
       GemmDims d{};
       d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
-      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = 8;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = kBandDW;
       EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
       ProfScope ps(RL_PROF_GEMM_DW, s);
       launch_gemm(dST, XT, d, e, 0, s);
