@@ -24,8 +24,8 @@ PEAK_F32_TFLOPS = 157.3
 # HBM-side bytes (L2 <-> fabric; FETCH_SIZE x2.0 + WRITE_SIZE x1.0 after calibration against a plain 1 GiB copy)
 # of one full 32768-row launch of each contraction class on the default workload, from two rocprofv3 --pmc runs
 # whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
-MEASURED_TRAFFIC_7B_CHUNK32768 = {"gemm_fwd": 56.6e9 + 0.2e9, "gemm_ds": 53.2e9 + 20.9e9,
-                                  "gemm_dx": 82.5e9 + 0.2e9, "gemm_dw": 73.3e9 + 2.2e9}
+MEASURED_TRAFFIC_7B_CHUNK32768 = {"gemm_fwd": 58.3e9 + 0.2e9, "gemm_ds": 53.5e9 + 20.9e9,
+                                  "gemm_dx": 57.3e9 + 0.2e9, "gemm_dw": 69.9e9 + 2.2e9}
 CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 8, "7b": 160, "long": 640, "32b": 768}   # ~10-30 s of oracle work
 
 
