@@ -108,6 +108,7 @@ typedef struct rl_outputs {     /* NULL = not wanted, except loss               
   float*    d_weight;           /* [V,H] f32, overwritten                                */
   float*    d_log_z;            /* [P]   zero for GRPO                                   */
   rl_stats* stats;              /* [1]                                                   */
+  float*    entropy;            /* [R]   entropy of softmax(W x_t), from the forward pass' online sums */
 } rl_outputs;
 
 /* Bytes of device workspace the two calls below need for this batch shape (host only; reads

@@ -75,6 +75,29 @@ def token_logprob(hidden, weight, token_ids, mask):
     return logp, lse
 
 
+def token_entropy(hidden, weight, mask):
+    """Entropy of the full next-token distribution, H_t = -sum_v p_v log p_v with p = softmax(W x_t)
+    (0 log 0 = 0), written out from the definition.  Masked rows give 0."""
+    X = widen(hidden)
+    W = widen(weight)
+    m = np.asarray(mask).astype(bool)
+    R = X.shape[0]
+    ent = np.zeros(R)
+    for s in range(0, R, ROW_BLOCK):
+        e = min(R, s + ROW_BLOCK)
+        rows = np.nonzero(m[s:e])[0] + s
+        if rows.size == 0:
+            continue
+        Z = X[rows] @ W.T
+        Z = Z - Z.max(axis=1, keepdims=True)
+        P = np.exp(Z)
+        P /= P.sum(axis=1, keepdims=True)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            term = np.where(P > 0, P * np.log(P), 0.0)
+        ent[rows] = -term.sum(axis=1)
+    return ent
+
+
 def segment_lengths(mask, cu_seqlens):
     """|y_i|: number of mask=1 rows of each sequence (integer, exact)."""
     m = np.asarray(mask).astype(np.int64)
@@ -217,7 +240,7 @@ GRPO, FLOW = 0, 1
 def policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx,
                         rewards, old_logprob, ref_logprob, log_z, P,
                         clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
-                        want_dw=True, want_grads=True):
+                        want_dw=True, want_grads=True, want_entropy=False):
     """The whole path in the order of the problem statement: log-prob, per-sequence lengths,
     group-relative advantage, loss + per-token coefficient, backward through the LM head."""
     logp, lse = token_logprob(hidden, weight, token_ids, mask)
@@ -232,6 +255,8 @@ def policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, 
     else:
         raise ValueError("objective")
     out.update(logprob=logp, lse=lse, seq_len=seq_len, advantages=adv)
+    if want_entropy:
+        out["entropy"] = token_entropy(hidden, weight, mask)
     if want_grads:
         dX, dW = lm_head_backward(hidden, weight, token_ids, mask, lse, out["c"], want_dw)
         out["d_hidden"] = dX

@@ -42,7 +42,8 @@ class rl_stats(C.Structure):
 class rl_outputs(C.Structure):
     _fields_ = [("loss", C.c_void_p), ("seq_loss", C.c_void_p), ("logprob", C.c_void_p), ("lse", C.c_void_p),
                 ("advantages", C.c_void_p), ("seq_len", C.c_void_p), ("coeff", C.c_void_p),
-                ("d_hidden", C.c_void_p), ("d_weight", C.c_void_p), ("d_log_z", C.c_void_p), ("stats", C.c_void_p)]
+                ("d_hidden", C.c_void_p), ("d_weight", C.c_void_p), ("d_log_z", C.c_void_p), ("stats", C.c_void_p),
+                ("entropy", C.c_void_p)]
 
 
 PROF_CLASSES = ("prep", "gemm_fwd", "combine", "loss", "transpose", "gemm_ds", "gemm_dx", "gemm_dw")
@@ -188,6 +189,7 @@ class LossResult:
     d_weight: Optional[torch.Tensor]
     d_log_z: torch.Tensor
     stats: torch.Tensor          # int32[8]: see STATS_FIELDS
+    entropy: Optional[torch.Tensor] = None
 
     def stats_dict(self):
         v = self.stats.cpu().tolist()
@@ -206,7 +208,8 @@ class PolicyLossPlan:
             seq_len=torch.empty(B, dtype=torch.int32, device=device), coeff=torch.empty(R, **f32),
             d_hidden=torch.empty((R, H), dtype=hidden_dtype, device=device) if backward else None,
             d_weight=torch.empty((V, H), **f32) if backward else None,
-            d_log_z=torch.empty(P, **f32), stats=torch.zeros(8, dtype=torch.int32, device=device))
+            d_log_z=torch.empty(P, **f32), stats=torch.zeros(8, dtype=torch.int32, device=device),
+            entropy=torch.empty(R, **f32))
         self.ws = _workspace(rl_workspace_bytes(batch, params, backward), device)
         o = rl_outputs()
         r = self.res
@@ -215,6 +218,7 @@ class PolicyLossPlan:
         o.d_hidden = r.d_hidden.data_ptr() if backward else None
         o.d_weight = r.d_weight.data_ptr() if backward else None
         o.d_log_z, o.stats = r.d_log_z.data_ptr(), r.stats.data_ptr()
+        o.entropy = r.entropy.data_ptr()
         self.out = o
         self.batch, self.params = batch, params
 

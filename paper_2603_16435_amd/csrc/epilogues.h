@@ -14,20 +14,21 @@ template <class T> __device__ inline float fast_exp(float x);
 template <> __device__ inline float fast_exp<bf16_t>(float x) { return __expf(x); }
 template <> __device__ inline float fast_exp<float>(float x) { return expf(x); }
 
-// ---- forward: per-token partial (max, sum exp) over this tile's vocab range + target gather
-//      z_t[y_t] is written by the single lane that holds vocab row y_t of token t.
+// ---- forward: per-token partial (max m, s = sum exp(z-m), u = sum exp(z-m) z) over this tile's vocab
+//      range + target gather; z_t[y_t] is written by the single lane that holds vocab row y_t of token t.
+//      u feeds the entropy H_t = lse_t - u/s of the full distribution at no extra pass.
 template <class T>
 struct EpiFwd {
   __device__ void keep_alive() const { zy_c[0] = 0.f; }
   const int* ids_c;     // [chunk-global compact row] sampled token
   float* zy_c;          // [compact row] target logit
-  float2* part;         // [tiles_m(V)][ldp] partial (max, sumexp) per token
+  float4* part;         // [tiles_m(V)][ldp] partial (m, s, u, -) per token
   int ldp;              // = chunk rows
   int V;
 
   template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
-    float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
+    float4* red = reinterpret_cast<float4*>(smem);              // [WAVES_M][BN]
     const float NEG = -__builtin_inff();
 #pragma unroll
     for (int bj = 0; bj < NB; ++bj) {
@@ -45,32 +46,38 @@ struct EpiFwd {
           mx = fmaxf(mx, (m < V) ? v : NEG);
         }
       const float ms = (mx == NEG) ? 0.f : mx;
-      float sm = 0.f;
+      float sm = 0.f, su = 0.f;
 #pragma unroll
       for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int m = c.m0 + acc_row(bi, i, c.lane);
-          const float e = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], i) - ms);
-          sm += (m < V) ? e : 0.f;
+          const float z = acc_read<AGPR>(acc[bi][bj], i);
+          const float e = (m < V) ? fast_exp<T>(z - ms) : 0.f;
+          sm += e;
+          su += (m < V) ? e * z : 0.f;
         }
-      const float mx2 = __shfl_xor(mx, 32), sm2 = __shfl_xor(sm, 32);
+      const float mx2 = __shfl_xor(mx, 32), sm2 = __shfl_xor(sm, 32), su2 = __shfl_xor(su, 32);
       const float mm = fmaxf(mx, mx2);
       const float mms = (mm == NEG) ? 0.f : mm;
-      sm = sm * fast_exp<T>(mx - mms) + sm2 * fast_exp<T>(mx2 - mms);
-      if (c.lane < 32) red[c.wm * BN + (n - c.tile_n * BN)] = make_float2(mm, sm);
+      const float f1 = fast_exp<T>(mx - mms), f2 = fast_exp<T>(mx2 - mms);
+      sm = sm * f1 + sm2 * f2;
+      su = su * f1 + su2 * f2;
+      if (c.lane < 32) red[c.wm * BN + (n - c.tile_n * BN)] = make_float4(mm, sm, su, 0.f);
     }
     __syncthreads();
     if (c.tid < BN) {
       const int n = c.tile_n * BN + c.tid;
       if (n < c.Nv) {
-        float2 r = red[c.tid];
+        float4 r = red[c.tid];
 #pragma unroll
         for (int w = 1; w < WAVES_M; ++w) {
-          const float2 o = red[w * BN + c.tid];
+          const float4 o = red[w * BN + c.tid];
           const float mm = fmaxf(r.x, o.x);
           const float mms = (mm == NEG) ? 0.f : mm;
-          r.y = r.y * fast_exp<T>(r.x - mms) + o.y * fast_exp<T>(o.x - mms);
+          const float f1 = fast_exp<T>(r.x - mms), f2 = fast_exp<T>(o.x - mms);
+          r.y = r.y * f1 + o.y * f2;
+          r.z = r.z * f1 + o.z * f2;
           r.x = mm;
         }
         part[(int64_t)c.tile_m * ldp + n] = r;

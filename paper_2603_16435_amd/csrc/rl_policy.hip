@@ -230,39 +230,49 @@ __global__ void advantage_kernel(const float* rewards, const int32_t* group_idx,
 // Fold the per-vocab-tile partials (max, sumexp) of a chunk into lse, logp.  A workgroup handles 64
 // compact rows x 4 slices of the tile range: one online (rescaling) pass per thread, coalesced
 // along the rows, then the four slices are merged through LDS in a fixed order.
-__global__ void lse_combine_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c,
+__global__ void lse_combine_kernel(const float4* part, int ldp, int tiles_v, const float* zy_c,
                                    const int32_t* row_map, const Ctrl* ctrl, int chunk_start, int chunk_rows,
-                                   float* lse_c, float* logp_c, float* lse_out, float* logp_out) {
-  __shared__ float sm[4][64], ss[4][64];
+                                   float* lse_c, float* logp_c, float* lse_out, float* logp_out, float* ent_out) {
+  __shared__ float sm[4][64], ss[4][64], su[4][64];
   int left = ctrl->n_real - chunk_start;
   if (left > chunk_rows) left = chunk_rows;
   if ((int)blockIdx.x * 64 >= left) return;
   const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + col;
   const float NEG = -__builtin_inff();
-  float m = NEG, s = 0.f;
+  float m = NEG, s = 0.f, u = 0.f;
   if (n < left) {
     for (int t = slice; t < tiles_v; t += 4) {
-      const float2 v = part[(int64_t)t * ldp + n];
+      const float4 v = part[(int64_t)t * ldp + n];
       const float mm = fmaxf(m, v.x);
-      if (mm != NEG) s = s * expf(m - mm) + v.y * expf(v.x - mm);
+      if (mm != NEG) {
+        const float f1 = expf(m - mm), f2 = expf(v.x - mm);
+        s = s * f1 + v.y * f2;
+        u = u * f1 + v.z * f2;
+      }
       m = mm;
     }
   }
-  sm[slice][col] = m; ss[slice][col] = s;
+  sm[slice][col] = m; ss[slice][col] = s; su[slice][col] = u;
   __syncthreads();
   if (slice == 0 && n < left) {
     float M = sm[0][col];
     for (int k = 1; k < 4; ++k) M = fmaxf(M, sm[k][col]);
-    double S = 0.0;
-    for (int k = 0; k < 4; ++k) if (sm[k][col] != NEG) S += (double)ss[k][col] * exp((double)(sm[k][col] - M));
-    const float lse = (float)((double)M + log(S));
+    double S = 0.0, U = 0.0;
+    for (int k = 0; k < 4; ++k)
+      if (sm[k][col] != NEG) {
+        const double f = exp((double)(sm[k][col] - M));
+        S += (double)ss[k][col] * f; U += (double)su[k][col] * f;
+      }
+    const double lse_d = (double)M + log(S);
+    const float lse = (float)lse_d;
     const int g = chunk_start + n;
     const float lp = zy_c[g] - lse;
     lse_c[g] = lse; logp_c[g] = lp;
     const int r = row_map[g];
     if (lse_out) lse_out[r] = lse;
     if (logp_out) logp_out[r] = lp;
+    if (ent_out) ent_out[r] = (float)fmax(lse_d - U / S, 0.0);     // H = lse - sum_v p_v z_v
   }
 }
 
@@ -432,7 +442,7 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   p.off_row_map = take(4 * Rp); p.off_ids_c = take(4 * Rp); p.off_cpos = take(4 * Rp);
   p.off_zy = take(4 * Rp); p.off_lse_c = take(4 * Rp); p.off_logp_c = take(4 * Rp); p.off_c_c = take(4 * Rp);
   p.off_adv = take(4 * (size_t)b->B); p.off_seq_loss = take(4 * (size_t)b->B); p.off_gterm = take(4 * (size_t)b->B);
-  p.off_part = take(sizeof(float2) * (size_t)p.tiles_v * (size_t)tc);
+  p.off_part = take(sizeof(float4) * (size_t)p.tiles_v * (size_t)tc);
   p.off_wt = p.off_xt = p.off_ds = p.off_dst = 0;
   if (bwd) {
     p.off_wt = take(p.esz * (size_t)b->H * (size_t)p.Vp);
@@ -475,7 +485,7 @@ static void launch_gemm(const float* A, const float* B, const GemmDims& d, const
 
 struct Ptrs {
   Ctrl* ctrl; int32_t *seq_len, *cstart, *row_map, *ids_c, *cpos;
-  float *zy, *lse_c, *logp_c, *c_c, *adv, *seq_loss, *gterm; float2* part;
+  float *zy, *lse_c, *logp_c, *c_c, *adv, *seq_loss, *gterm; float4* part;
   void *wt, *xt, *ds, *dst;
 };
 
@@ -486,7 +496,7 @@ static Ptrs carve(void* ws, const Plan& p) {
   q.row_map = (int32_t*)(w + p.off_row_map); q.ids_c = (int32_t*)(w + p.off_ids_c); q.cpos = (int32_t*)(w + p.off_cpos);
   q.zy = (float*)(w + p.off_zy); q.lse_c = (float*)(w + p.off_lse_c); q.logp_c = (float*)(w + p.off_logp_c);
   q.c_c = (float*)(w + p.off_c_c); q.adv = (float*)(w + p.off_adv); q.seq_loss = (float*)(w + p.off_seq_loss);
-  q.gterm = (float*)(w + p.off_gterm); q.part = (float2*)(w + p.off_part);
+  q.gterm = (float*)(w + p.off_gterm); q.part = (float4*)(w + p.off_part);
   q.wt = w + p.off_wt; q.xt = w + p.off_xt; q.ds = w + p.off_ds; q.dst = w + p.off_dst;
   return q;
 }
@@ -505,7 +515,7 @@ static void run_prep(const rl_batch* b, const Plan& p, const Ptrs& q, int32_t* s
 }
 
 template <class T>
-static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* logp_out, float* lse_out, hipStream_t s) {
+static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* logp_out, float* lse_out, float* ent_out, hipStream_t s) {
   const T* X = static_cast<const T*>(b->hidden);
   const T* W = static_cast<const T*>(b->weight);
   for (int ch = 0; ch < p.n_chunks; ++ch) {
@@ -517,7 +527,7 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm(W, X, d, e, kPrefetchLogits, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
     lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
-                                                        q.lse_c, q.logp_c, lse_out, logp_out);
+                                                        q.lse_c, q.logp_c, lse_out, logp_out, ent_out);
   }
 }
 
@@ -614,7 +624,7 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 100; }
+int32_t rl_version(void) { return 101; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
 
 rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params, int32_t want_backward, size_t* bytes) {
@@ -639,8 +649,8 @@ rl_status rl_token_logprob(const rl_batch* b, float* logprob, float* lse, void* 
   (void)hipGetLastError();
   Ptrs q = carve(ws, p);
   run_prep(b, p, q, nullptr, nullptr, nullptr, logprob, lse, nullptr, s);
-  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, logprob, lse, s);
-  else run_forward<float>(b, p, q, logprob, lse, s);
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, logprob, lse, nullptr, s);
+  else run_forward<float>(b, p, q, logprob, lse, nullptr, s);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 
@@ -667,6 +677,7 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   Ptrs q = carve(ws, p);
 
   run_prep(b, p, q, out->seq_len, out->stats, b->group_idx, out->logprob, out->lse, out->coeff, s);
+  fill<float>(out->entropy, p.R, 0.f, s);
   {
   ProfScope ps(RL_PROF_LOSS, s);
   fill<float>(q.adv, p.B, 0.f, s);
@@ -674,8 +685,8 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   if (out->advantages) (void)hipMemcpyAsync(out->advantages, q.adv, 4 * (size_t)p.B, hipMemcpyDeviceToDevice, s);
   }
 
-  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, out->logprob, out->lse, s);
-  else run_forward<float>(b, p, q, out->logprob, out->lse, s);
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, out->logprob, out->lse, out->entropy, s);
+  else run_forward<float>(b, p, q, out->logprob, out->lse, out->entropy, s);
 
   {
   ProfScope ps(RL_PROF_LOSS, s);

@@ -35,6 +35,7 @@ def run_oracle(b, objective: str, want_dw=True, **over):
     inp = oracle_inputs(b)
     return orc.policy_loss_fwd_bwd(OBJ[objective][0], cu_seqlens=np_bits(b.cu_seqlens), group_idx=np_bits(b.group_idx),
                                    rewards=np_bits(b.rewards), log_z=np_bits(b.log_z), P=c.P, want_dw=want_dw,
+                                   want_entropy=True,
                                    **inp, **kw)
 
 
@@ -75,6 +76,11 @@ def compare_all(b, res, ref, *, loss_tol, logp_atol, grad_tol, check_dw=True):
     err["logp"] = float(np.abs(lp - ref["logprob"]).max())
     err["lse"] = float(np.abs(lse - ref["lse"]).max())
     assert err["logp"] <= logp_atol and err["lse"] <= logp_atol, err
+    if "entropy" in ref:
+        ent = f64(res.entropy)
+        assert np.all(ent[~m] == 0)
+        err["entropy"] = float(np.abs(ent - ref["entropy"]).max())
+        assert err["entropy"] <= logp_atol, err
     np.testing.assert_allclose(f64(res.advantages), ref["advantages"], atol=2e-6, rtol=1e-6)
     err["loss"] = loss_rel_err(float(res.loss.item()), ref)
     sl_scale = max(float(np.abs(ref["seq_loss"]).max()), 1e-30)

@@ -194,6 +194,7 @@ def test_7b_full_size_sampled_sequences():
     ones = np.ones(rows.size, np.uint8)
     cu_s = np.concatenate([[0], np.cumsum(lengths[pick])])
     lp_ref, lse_ref = orc.token_logprob(Xs, W, ids_s, ones)
+    ent_ref = orc.token_entropy(Xs, W, ones)
     adv_ref = orc.group_advantage(np_bits(b.rewards), np_bits(b.group_idx), c.P, c.adv_eps, c.adv_std_ddof)
     gidx = np_bits(b.group_idx).astype(np.int64)
     X64 = None
@@ -207,6 +208,7 @@ def test_7b_full_size_sampled_sequences():
         # the sampled sequences, element by element
         assert np.abs(f64(res.logprob[rows_t]) - lp_ref).max() <= BF16_TOL["logp_atol"]
         assert np.abs(f64(res.lse[rows_t]) - lse_ref).max() <= BF16_TOL["logp_atol"]
+        assert np.abs(f64(res.entropy[rows_t]) - ent_ref).max() <= BF16_TOL["logp_atol"]
         if objective == "grpo":
             o = orc.grpo_loss(lp_ref, old_s, ref_s, ones, cu_s, adv_ref[pick], c.clip_eps, c.kl_coef)
         else:

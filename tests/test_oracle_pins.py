@@ -146,6 +146,33 @@ def test_logprob_closed_forms_and_invariants():
     np.testing.assert_allclose(lb - la, 7.5, atol=1e-12)
 
 
+def test_entropy_pins():
+    import scipy.stats
+    rng = np.random.default_rng(31)
+    X, W, ids = _rand_problem(rng, R=9, H=5, V=13)
+    mask = np.array([1, 1, 1, 0, 1, 1, 0, 1, 1], dtype=np.uint8)
+    ent = orc.token_entropy(X, W, mask)
+    P = scipy.special.softmax(X @ W.T, axis=1)
+    ref = scipy.stats.entropy(P, axis=1)                       # independent library routine
+    np.testing.assert_allclose(ent[mask.astype(bool)], ref[mask.astype(bool)], atol=1e-13)
+    assert np.all(ent[~mask.astype(bool)] == 0)
+    # H = lse - sum_v p_v z_v (the identity the online version uses)
+    lp, lse = orc.token_logprob(X, W, ids, np.ones(9, np.uint8))
+    np.testing.assert_allclose(orc.token_entropy(X, W, np.ones(9, np.uint8)), lse - (P * (X @ W.T)).sum(1), atol=1e-12)
+    # closed forms: uniform -> ln V; one dominant logit a, V-1 zeros -> lse - a p_y
+    np.testing.assert_allclose(orc.token_entropy(X, np.zeros_like(W), np.ones(9, np.uint8)), math.log(13), atol=1e-14)
+    Wd = np.zeros((13, 5)); Wd[4, 0] = 3.0
+    Xd = np.zeros((1, 5)); Xd[0, 0] = 1.0
+    lse_d = math.log(math.exp(3.0) + 12)
+    assert orc.token_entropy(Xd, Wd, [1])[0] == pytest.approx(lse_d - 3.0 * math.exp(3.0 - lse_d), rel=1e-13)
+    # bounds and invariance to a shift of every logit; an extreme logit gives exactly 0 without NaN
+    assert np.all(ent >= 0) and np.all(ent <= math.log(13) + 1e-12)
+    X1 = np.concatenate([X, np.ones((9, 1))], 1); W1 = np.concatenate([W, np.full((13, 1), -4.0)], 1)
+    np.testing.assert_allclose(orc.token_entropy(X1, W1, mask), ent, atol=1e-12)
+    Wd[4, 0] = 2000.0
+    assert orc.token_entropy(Xd, Wd, [1])[0] == 0.0
+
+
 def test_masked_rows_are_ignored():
     rng = np.random.default_rng(3)
     X, W, ids = _rand_problem(rng, R=12, H=5, V=7)
