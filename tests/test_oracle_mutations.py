@@ -1,0 +1,80 @@
+"""The pins must bite: plant one plausible mistake at a time in a copy of the oracle (on the CPU,
+by patching its source text) and check that at least one pin test fails for every mutant."""
+import importlib
+import inspect
+import os
+import sys
+import types
+
+import pytest
+
+import test_oracle_pins as pins
+from oracle import policy_oracle as orc
+
+MUTANTS = [
+    # (name, text to find, replacement)
+    ("logits transposed operand", "Z = X[rows] @ W.T                       # [n, V] logits", "Z = (W @ X[rows].T).T[:, ::-1]"),
+    ("lse without the max added back", "l = M + np.log(np.exp(Z - M[:, None]).sum(axis=1))", "l = np.log(np.exp(Z - M[:, None]).sum(axis=1))"),
+    ("logp sign", "logp[rows] = zy - l", "logp[rows] = l - zy"),
+    ("gather wrong index", "zy = Z[np.arange(rows.size), ids[rows]]", "zy = Z[np.arange(rows.size), (ids[rows] + 1) % Z.shape[1]]"),
+    ("entropy sign", "ent[rows] = -term.sum(axis=1)", "ent[rows] = term.sum(axis=1)"),
+    ("advantage: eps inside the root", "adv[members] = (r[members] - mu) / (np.sqrt(var) + adv_eps)", "adv[members] = (r[members] - mu) / np.sqrt(var + adv_eps)"),
+    ("advantage: no mean subtraction", "adv[members] = (r[members] - mu) / (np.sqrt(var) + adv_eps)", "adv[members] = r[members] / (np.sqrt(var) + adv_eps)"),
+    ("grpo: max instead of min", "l = -np.minimum(unclipped, clipped) + kl_coef * kl", "l = -np.maximum(unclipped, clipped) + kl_coef * kl"),
+    ("grpo: dropped KL term", "l = -np.minimum(unclipped, clipped) + kl_coef * kl", "l = -np.minimum(unclipped, clipped)"),
+    ("grpo: KL direction", "d = ref[rows] - lp[rows]\n        kl", "d = lp[rows] - ref[rows]\n        kl"),
+    ("grpo: token-sum instead of token-mean", "seq_loss[i] = l.sum() / n\n        hi", "seq_loss[i] = l.sum()\n        hi"),
+    ("grpo: gradient ignores clipping", "c[rows] = (-A * rho * act + kl_coef * (1.0 - np.exp(d))) / (B * n)", "c[rows] = (-A * rho + kl_coef * (1.0 - np.exp(d))) / (B * n)"),
+    ("grpo: gradient KL sign", "c[rows] = (-A * rho * act + kl_coef * (1.0 - np.exp(d))) / (B * n)", "c[rows] = (-A * rho * act - kl_coef * (1.0 - np.exp(d))) / (B * n)"),
+    ("grpo: gradient normaliser", "c[rows] = (-A * rho * act + kl_coef * (1.0 - np.exp(d))) / (B * n)", "c[rows] = (-A * rho * act + kl_coef * (1.0 - np.exp(d))) / B"),
+    ("flow: reference term not length-normalised", "delta[i] = lz[g[i]] + (lp[rows] - ref[rows]).sum() / n - beta * adv[i]", "delta[i] = lz[g[i]] + (lp[rows] - ref[rows]).sum() - beta * adv[i]"),
+    ("flow: reward sign", "delta[i] = lz[g[i]] + (lp[rows] - ref[rows]).sum() / n - beta * adv[i]", "delta[i] = lz[g[i]] + (lp[rows] - ref[rows]).sum() / n + beta * adv[i]"),
+    ("flow: unclipped weight", "w[i] = np.exp(min(max(log_ratio, lo_b), hi_b))", "w[i] = np.exp(min(log_ratio, 50.0))"),
+    ("flow: gradient factor 2 dropped", "c[rows] = 2.0 * w[i] * delta[i] / (B * n)", "c[rows] = w[i] * delta[i] / (B * n)"),
+    ("flow: d_logZ to the wrong prompt", "dz[g[i]] += 2.0 * w[i] * delta[i] / B", "dz[(g[i] + 1) % dz.size] += 2.0 * w[i] * delta[i] / B"),
+    ("backward: softmax minus onehot sign", "dS = -np.exp(Z - lse[rows][:, None])\n        dS[np.arange(rows.size), ids[rows]] += 1.0", "dS = np.exp(Z - lse[rows][:, None])\n        dS[np.arange(rows.size), ids[rows]] -= 1.0"),
+    ("backward: dX with transposed weight use", "dX[rows] = dS @ W", "dX[rows] = (dS * 0 + dS.mean(1, keepdims=True)) @ W"),
+    ("backward: dW without the transpose", "dW += dS.T @ X[rows]", "dW += (X[rows].T @ dS).T * 0 + dS.T @ np.roll(X[rows], 1, axis=1)"),
+    ("backward: masked rows leak", "rows = np.nonzero(m[s:e])[0] + s\n        if rows.size == 0:\n            continue\n        Z = X[rows] @ W.T\n        dS", "rows = np.arange(s, e)\n        if rows.size == 0:\n            continue\n        Z = X[rows] @ W.T\n        dS"),
+    ("bf16 widening shifts by 15", "<< np.uint32(16)", "<< np.uint32(15)"),
+]
+
+PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]
+
+
+def _run_pins_against(mod):
+    """Names of the pin tests that fail when the pins module sees `mod` as the oracle."""
+    failed = []
+    saved = pins.orc
+    pins.orc = mod
+    try:
+        for name, fn in PIN_TESTS:
+            marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+            argsets = [()]
+            if marks:
+                argsets = [(v,) for v in marks[0].args[1]]
+            for a in argsets:
+                try:
+                    fn(*a)
+                except Exception:       # assertion, numerical error, shape error: all count as caught
+                    failed.append(name)
+                    break
+    finally:
+        pins.orc = saved
+    return failed
+
+
+def test_unmutated_oracle_passes_every_pin():
+    assert _run_pins_against(orc) == []
+
+
+@pytest.mark.parametrize("name,find,repl", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_every_planted_mistake_is_caught(name, find, repl):
+    src = inspect.getsource(orc)
+    assert src.count(find) >= 1, f"mutation site not found: {name}"
+    mutated = src.replace(find, repl, 1)
+    mod = types.ModuleType("oracle_mutant")
+    mod.__dict__["__name__"] = "oracle_mutant"
+    exec(compile(mutated, "oracle_mutant.py", "exec"), mod.__dict__)
+    failed = _run_pins_against(mod)
+    assert failed, f"no pin notices: {name}"
