@@ -106,6 +106,10 @@ def main():
     prof = binding.rl_profile_read()
     binding.rl_profile_enable(False)
 
+    # what a pure MFMA loop with toggling random operands reaches on this part right now (no memory traffic)
+    peak_burst = binding.rl_measure_mfma_peak(200, dev)
+    peak_sustained = binding.rl_measure_mfma_peak(1000, dev)
+
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
@@ -150,6 +154,9 @@ def main():
                      "traffic_note": "bytes per full 32768-row launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
                      "flops_per_full_launch": 2.0 * 32768 * cfg.H * cfg.V,
                      "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": int(dom_n)},
+        "mfma_only_measured": {"burst_200ms": {"tflops": peak_burst[0], "shader_mhz": peak_burst[1]},
+                               "sustained_1s": {"tflops": peak_sustained[0], "shader_mhz": peak_sustained[1]},
+                               "roofline_frac_of_sustained": achieved / peak_sustained[0] if peak_sustained[0] > 0 else None},
         "kernels": kernels,
         "loss": loss,
     }

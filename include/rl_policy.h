@@ -157,6 +157,14 @@ rl_status rl_profile_read(rl_profile* out);
 int32_t rl_version(void);
 int32_t rl_default_chunk_rows(void);
 
+/* Benchmark aid: runs a pure bf16 MFMA issue loop (v_mfma_f32_32x32x16_bf16, 16 independent
+ * accumulators per wavefront, four wavefronts per CU, no memory traffic) for about `millis` ms on
+ * `stream`, SYNCHRONISES on it, and returns the rate it reached and the shader clock it ran at.  This is
+ * the ceiling any MFMA-bound kernel can approach on this part at this moment (clock throttling included).
+ * scratch: device buffer of at least 1 MiB owned by the caller. */
+rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
+                               double* tflops, double* shader_mhz);
+
 #ifdef __cplusplus
 }
 #endif

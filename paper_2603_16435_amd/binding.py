@@ -85,6 +85,8 @@ def lib() -> C.CDLL:
         L.rl_profile_enable.restype = None
         L.rl_profile_read.argtypes = [C.POINTER(rl_profile)]
         L.rl_profile_read.restype = C.c_int
+        L.rl_measure_mfma_peak.argtypes = [C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.rl_measure_mfma_peak.restype = C.c_int
         L.rl_version.restype = C.c_int32
         L.rl_default_chunk_rows.restype = C.c_int32
         _lib = L
@@ -254,3 +256,11 @@ def rl_profile_read() -> dict:
     pr = rl_profile()
     _check(lib().rl_profile_read(C.byref(pr)))
     return {name: (pr.ms[i], pr.launches[i]) for i, name in enumerate(PROF_CLASSES)}
+
+
+def rl_measure_mfma_peak(millis: int = 200, device="cuda:0"):
+    """(TFLOP/s, shader MHz) of a pure bf16 MFMA issue loop run for about `millis` ms (synchronises)."""
+    buf = torch.empty(2 << 20, dtype=torch.uint8, device=device)
+    t, m = C.c_double(0), C.c_double(0)
+    _check(lib().rl_measure_mfma_peak(millis, buf.data_ptr(), buf.numel(), _stream_handle(), C.byref(t), C.byref(m)))
+    return t.value, m.value

@@ -404,6 +404,39 @@ __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int col
   }
 }
 
+// ------------------------------------------------------------------ MFMA ceiling probe (benchmark aid)
+__global__ __launch_bounds__(256) void mfma_peak_kernel(float* out, int iters, long long* clk) {
+  floatx16 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  // operands: pseudo-random bf16 values in (-1,1), two sets alternated so that the inputs toggle the
+  // way real data does (constant operands let the part hold 2.4 GHz; real ones do not)
+  bf16x8 a[2], b[2];
+  unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      h = h * 1664525u + 1013904223u; a[k][e] = (bf16_t)(((int)(h >> 8) & 0xffff) * (1.f / 32768.f) - 1.f);
+      h = h * 1664525u + 1013904223u; b[k][e] = (bf16_t)(((int)(h >> 8) & 0xffff) * (1.f / 32768.f) - 1.f);
+    }
+  const long long t0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 1], b[(i >> 1) & 1], acc[i], 0, 0, 0);
+  }
+  const long long t1 = clock64(), w1 = wall_clock64();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+  if (threadIdx.x == 0) { clk[blockIdx.x * 2] = t1 - t0; clk[blockIdx.x * 2 + 1] = w1 - w0; }
+}
+
 // ------------------------------------------------------------------ host side
 struct Plan {
   int64_t R; int H, V, B, P; int dtype; size_t esz;
@@ -626,6 +659,37 @@ rl_status rl_profile_read(rl_profile* out) {
 
 int32_t rl_version(void) { return 101; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
+
+rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
+                               double* tflops, double* shader_mhz) {
+  if (!scratch || !tflops || !shader_mhz) return RL_ERR_NULL;
+  if (millis < 1 || millis > 5000) return RL_ERR_RANGE;
+  constexpr int kBlocks = 1024;                                   // 4 workgroups of 4 wavefronts per CU
+  if (scratch_bytes < (size_t)kBlocks * 256 * 4 + (size_t)kBlocks * 16 || (reinterpret_cast<uintptr_t>(scratch) & 15)) return RL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* out = static_cast<float*>(scratch);
+  long long* clk = reinterpret_cast<long long*>(out + kBlocks * 256);
+  // one launch of `iters` rounds of 16 MFMAs per wavefront: ~32 cycles per MFMA, 4 workgroups share a CU
+  const double cycles_per_round = 16.0 * 32.0 * 4.0;
+  int iters = (int)(millis * 1e-3 * 2.0e9 / cycles_per_round);
+  if (iters < 16) iters = 16;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return RL_ERR_HIP;
+  mfma_peak_kernel<<<kBlocks, 256, 0, s>>>(out, 16, clk);        // warm-up
+  (void)hipEventRecord(e0, s);
+  mfma_peak_kernel<<<kBlocks, 256, 0, s>>>(out, iters, clk);
+  (void)hipEventRecord(e1, s);
+  rl_status st = RL_OK;
+  float ms = 0.f;
+  if (hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f) st = RL_ERR_HIP;
+  long long h[2] = {0, 0};
+  if (st == RL_OK && hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) st = RL_ERR_HIP;
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  if (st != RL_OK) return st;
+  *tflops = (double)kBlocks * 4.0 * iters * 16.0 * 32768.0 / (ms * 1e-3) / 1e12;
+  *shader_mhz = h[1] > 0 ? 100.0 * (double)h[0] / (double)h[1] : 0.0;   // wall clock ticks at 100 MHz
+  return RL_OK;
+}
 
 rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params, int32_t want_backward, size_t* bytes) {
   if (!batch || !bytes) return RL_ERR_NULL;
