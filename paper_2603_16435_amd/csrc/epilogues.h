@@ -1,10 +1,11 @@
 // epilogues.h - what each contraction does with its accumulators while they are in registers.
 //
 // Orientation.  The logits contraction is run "vocab-major": A = W (rows = vocab entries),
-// B = X (rows = tokens), so that in the 32x32 accumulator layout a lane owns ONE token column
-// and 16 vocab rows per block.  The softmax reductions over the vocabulary are then mostly
-// in-register; the only cross-lane step is between lanes l and l+32 (one shuffle), and the
-// only cross-wavefront step is between the WAVES_M wavefronts stacked along the vocabulary.
+// B = X (rows = tokens), so that in the MFMA accumulator layouts (see Layout32 / Layout16) a lane
+// owns ONE token column per block and several vocab rows of it.  The softmax reductions over the
+// vocabulary are then mostly in-register; the only cross-lane steps are between the lane groups
+// that hold other rows of the same column (one or two shuffles), and the only cross-wavefront
+// step is between the WAVES_M wavefronts stacked along the vocabulary.
 #pragma once
 #include "gemm_nt.h"
 
@@ -26,21 +27,21 @@ struct EpiFwd {
   int ldp;              // = chunk rows
   int V;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
+  template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
     float4* red = reinterpret_cast<float4*>(smem);              // [WAVES_M][BN]
     const float NEG = -__builtin_inff();
 #pragma unroll
     for (int bj = 0; bj < NB; ++bj) {
-      const int n = c.n0 + acc_col(bj, c.lane);
+      const int n = c.n0 + L::col(bj, c.lane);
       const bool valid = n < c.Nv;
       const int y = valid ? ids_c[d.chunk_start + n] : -1;
       float mx = NEG;
 #pragma unroll
       for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int m = c.m0 + acc_row(bi, i, c.lane);
+        for (int i = 0; i < L::kRegs; ++i) {
+          const int m = c.m0 + L::row(bi, i, c.lane);
           const float v = acc_read<AGPR>(acc[bi][bj], i);
           if (m == y) zy_c[d.chunk_start + n] = v;
           mx = fmaxf(mx, (m < V) ? v : NEG);
@@ -50,20 +51,25 @@ struct EpiFwd {
 #pragma unroll
       for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int m = c.m0 + acc_row(bi, i, c.lane);
+        for (int i = 0; i < L::kRegs; ++i) {
+          const int m = c.m0 + L::row(bi, i, c.lane);
           const float z = acc_read<AGPR>(acc[bi][bj], i);
           const float e = (m < V) ? fast_exp<T>(z - ms) : 0.f;
           sm += e;
           su += (m < V) ? e * z : 0.f;
         }
-      const float mx2 = __shfl_xor(mx, 32), sm2 = __shfl_xor(sm, 32), su2 = __shfl_xor(su, 32);
-      const float mm = fmaxf(mx, mx2);
-      const float mms = (mm == NEG) ? 0.f : mm;
-      const float f1 = fast_exp<T>(mx - mms), f2 = fast_exp<T>(mx2 - mms);
-      sm = sm * f1 + sm2 * f2;
-      su = su * f1 + su2 * f2;
-      if (c.lane < 32) red[c.wm * BN + (n - c.tile_n * BN)] = make_float4(mm, sm, su, 0.f);
+      // merge with the lane groups that hold the other rows of this column
+#pragma unroll
+      for (int off = L::kBlk; off < 64; off <<= 1) {
+        const float mx2 = __shfl_xor(mx, off), sm2 = __shfl_xor(sm, off), su2 = __shfl_xor(su, off);
+        const float mm = fmaxf(mx, mx2);
+        const float mms = (mm == NEG) ? 0.f : mm;
+        const float f1 = fast_exp<T>(mx - mms), f2 = fast_exp<T>(mx2 - mms);
+        sm = sm * f1 + sm2 * f2;
+        su = su * f1 + su2 * f2;
+        mx = mm;
+      }
+      if (c.lane < L::kBlk) red[c.wm * BN + (n - c.tile_n * BN)] = make_float4(mx, sm, su, 0.f);
     }
     __syncthreads();
     if (c.tid < BN) {
@@ -111,11 +117,11 @@ struct EpiDS {
   T* dST; int64_t ld_dst;   // [Vp][chunk rows]
   int V;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+  template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
 #pragma unroll
     for (int bj = 0; bj < NB; ++bj) {
-      const int n = c.n0 + acc_col(bj, c.lane);
+      const int n = c.n0 + L::col(bj, c.lane);
       const bool valid = n < c.Nv;
       const int g = d.chunk_start + n;
       const int y = valid ? ids_c[g] : -1;
@@ -124,8 +130,8 @@ struct EpiDS {
 #pragma unroll
       for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int m = c.m0 + acc_row(bi, q * 4, c.lane);
+        for (int q = 0; q < L::kRegs / 4; ++q) {
+          const int m = c.m0 + L::row(bi, q * 4, c.lane);
           float o[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -148,18 +154,18 @@ struct EpiDX {
   const int* row_map;   // compact row -> original row
   T* dX; int64_t ldx; int H;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+  template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int m = c.m0 + acc_row(bi, i, c.lane);
+      for (int i = 0; i < L::kRegs; ++i) {
+        const int m = c.m0 + L::row(bi, i, c.lane);
         if (m >= c.Mv) continue;
         const int64_t dst = row_map[d.chunk_start + m];
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj) {
-          const int n = c.n0 + acc_col(bj, c.lane);
+          const int n = c.n0 + L::col(bj, c.lane);
           if (n < H) dX[dst * ldx + n] = (T)acc_read<AGPR>(acc[bi][bj], i);
         }
       }
@@ -171,17 +177,17 @@ struct EpiDW {
   __device__ void keep_alive() const { dW[0] = 0.f; }
   float* dW; int64_t ldw; int V, H; int accumulate;
 
-  template <int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(floatx16 (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
+  template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int m = c.m0 + acc_row(bi, i, c.lane);
+      for (int i = 0; i < L::kRegs; ++i) {
+        const int m = c.m0 + L::row(bi, i, c.lane);
         if (m >= V) continue;
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj) {
-          const int n = c.n0 + acc_col(bj, c.lane);
+          const int n = c.n0 + L::col(bj, c.lane);
           if (n < H) {
             float* p = dW + (int64_t)m * ldw + n;
             const float v = acc_read<AGPR>(acc[bi][bj], i);

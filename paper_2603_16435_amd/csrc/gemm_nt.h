@@ -9,22 +9,22 @@
 // Two kernels share tile order, LDS layout and epilogues:
 //  * gemm_nt_bf16_kernel  - the hot one (bf16, K % 128 == 0).  256x256 tile, four wavefronts of
 //    128x128 each (256 accumulator registers per lane live in AGPRs, one wavefront per SIMD),
-//    K walked in slabs of 64.  Slabs go from global memory straight into LDS
-//    (global_load ... lds, 16 bytes per lane) into two static 64 KiB stages; the loads of a slab
-//    are spread over three k-steps so that no burst blocks the MFMA issue, fragments of k-step
-//    s+1 are read from LDS while k-step s feeds the MFMAs, and the last k-step of a slab runs
-//    after the workgroup barrier so that it hides the first fragment reads of the next slab.
-//    The interleaving is pinned with sched_group_barrier.  A light software prefetch (one 4-byte
-//    load per 128-byte line, a few slabs ahead, shared between the workgroups of an XCD) pulls
-//    the next panels into that XCD's L2.
+//    K walked in slabs of 64, MFMA shape 16x16x32 (measured on this part: at the power limit it
+//    sustains about 15 % more flops than 32x32x16 on random data).  Slabs go from global memory
+//    straight into LDS (global_load ... lds, 16 bytes per lane) into two static 64 KiB stages.  A
+//    slab is four phases of 32 MFMAs; its loads are spread over three phases so that no burst
+//    blocks the MFMA issue, the fragments of a phase are read from LDS during the phase before,
+//    and the last phase of a slab runs after the workgroup barrier so that it hides the first
+//    fragment reads of the next slab.  The MFMAs are inline asm and every one is fenced with
+//    sched_barrier, so the interleaving in the source is the interleaving issued.  A light
+//    software prefetch (one 4-byte load per 128-byte line, a few slabs ahead, shared between the
+//    workgroups of an XCD) pulls the next panels into that XCD's L2.
 //  * gemm_nt_kernel       - generic fallback (f32 inputs, or K not a multiple of 128): eight
-//    wavefronts of 128x64, register-staged loads with a K-tail predicate.
+//    wavefronts of 128x64, 32x32 MFMA blocks, register-staged loads with a K-tail predicate.
 //
 // LDS rows are 128 B = eight 16-byte chunks; chunk c of row r sits at slot c ^ ((r>>1)&7),
 // which spreads both the 16-byte row-wise stores and the column-wise fragment loads over all
-// 64 banks (measured: zero bank conflicts).  MFMA shape is 32x32 (x16 for bf16, x2 for f32);
-// both have the same accumulator layout: lane l, register i hold
-// row = 8*(i/4) + 4*(l/32) + i%4,  col = l%32.
+// 64 banks (measured: zero bank conflicts).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -35,6 +35,8 @@ typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kSlabBytes = 128;   // bytes of K per LDS row
 constexpr int kXcds = 8;          // MI355X: 8 accelerator dies, workgroups dealt round-robin
@@ -100,6 +102,37 @@ struct TileCtx {
   int tid;
 };
 template <int> struct Int {};
+
+// Accumulator layouts: where register i of block (bi, bj) of a lane sits inside the wavefront's
+// sub-tile.  Registers come in runs of four consecutive rows of one column.
+struct Layout32 {   // 32x32 MFMA blocks, 16 registers per block: row = 8*(i/4) + 4*(l/32) + i%4, col = l%32
+  typedef floatx16 acc_t;
+  static constexpr int kBlk = 32, kRegs = 16;
+  __device__ static int row(int bi, int i, int lane) { return bi * 32 + ((i >> 2) << 3) + ((lane >> 5) << 2) + (i & 3); }
+  __device__ static int col(int bj, int lane) { return bj * 32 + (lane & 31); }
+};
+struct Layout16 {   // 16x16 MFMA blocks, 4 registers per block: row = 4*(l/16) + i, col = l%16
+  typedef floatx4 acc_t;
+  static constexpr int kBlk = 16, kRegs = 4;
+  __device__ static int row(int bi, int i, int lane) { return bi * 16 + ((lane >> 4) << 2) + i; }
+  __device__ static int col(int bj, int lane) { return bj * 16 + (lane & 15); }
+};
+
+// Reading one accumulator element in an epilogue.  In the hot kernel the 256 accumulators of a lane
+// live in AGPRs; left to itself the compiler copies all of them to VGPRs at loop exit and spills
+// most of them to scratch (tens of GB of extra HBM traffic per launch).  Reading each element
+// through an explicit v_accvgpr_read at its point of use keeps them where they are.
+template <bool AGPR, class V>
+__device__ inline float acc_read(const V& v, int i) {
+  if constexpr (AGPR) {
+    float r;
+    const float e = v[i];
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(e));
+    return r;
+  } else {
+    return v[i];
+  }
+}
 
 template <class T, class Epi, int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64)
@@ -206,7 +239,7 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
   TileCtx c;
   c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
   c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
-  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N, false>(acc, c, smem, d);
+  epi.template run<Layout32, MB, NB, BM, BN, WAVES_M, WAVES_N, false>(acc, c, smem, d);
 }
 
 // ------------------------------------------------------------------ bf16 hot kernel
@@ -217,12 +250,26 @@ __device__ inline void load16_to_lds(const void* g, void* l) {   // 64 lanes x 1
   __builtin_amdgcn_global_load_lds((glb_ptr_t)g, (lds_ptr_t)l, 16, 0, 0);
 }
 
-template <class Epi, int PFD>   // PFD: L2 prefetch distance in slabs (0 = none)
+// One 16x16x32 bf16 MFMA, accumulator in place.  Written as inline asm so that the 64 accumulator
+// blocks of a lane are pinned to the 256 AGPRs for the whole kernel: with the builtin the register
+// allocator splits them between the two register files and fills the main loop with copies.  The
+// compiler therefore does not know these are MFMAs: the required wait states before the epilogue
+// reads the accumulators are inserted by hand (mfma_drain).
+__device__ __attribute__((always_inline)) inline void mfma16(floatx4& acc, const u32x4_t& a, const u32x4_t& b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __attribute__((always_inline)) inline void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
+
+// PFD: L2 prefetch distance in slabs (0 = none).  VMG / VMO: inside a phase of 32 MFMAs the slab loads
+// are issued after MFMA number VMO, VMO + VMG, VMO + 2 VMG, ...
+template <class Epi, int PFD, int VMG, int VMO>
 __global__ __launch_bounds__(256)
 void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, Epi epi) {
   constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2;
-  constexpr int WM = 128, WN = 128, MB = 4, NB = 4;
+  constexpr int WM = 128, WN = 128, MB = 8, NB = 8;             // 8 x 8 blocks of 16 x 16 per wavefront
+  constexpr int DSG = 2;                                        // one fragment read per DSG MFMAs
   constexpr int A_BYTES = BM * kSlabBytes, B_BYTES = BN * kSlabBytes, STAGE = A_BYTES + B_BYTES;
+  static_assert(VMO < VMG && 5 * VMG + VMO < 32, "six slab loads must fit into a phase");
   // two separate objects: the compiler can then tell the stage being filled by the DMA loads from the
   // stage the fragments are read from, and does not serialise them with a vmcnt(0)
   __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
@@ -263,16 +310,11 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
     if (d.b_rows) r = d.b_rows[r];
     bp[j] = B + (int64_t)r * d.ldb + c * 8;
   }
-  // loads j in [lo,hi) of the 16 per slab (0..7 = A rows, 8..15 = B rows)
-  auto issue = [&](int k0, unsigned char* stage, int lo, int hi) __attribute__((always_inline)) {
+  // load j of the 16 per slab (0..7 = A rows, 8..15 = B rows)
+  auto issue1 = [&](int k0, unsigned char* stage, int j) __attribute__((always_inline)) {
     unsigned char* as = stage + wave * 64 * kSlabBytes;
-    unsigned char* bs = as + A_BYTES;
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (j < lo || j >= hi) continue;
-      if (j < 8) load16_to_lds(ap[j] + k0, as + j * 8 * kSlabBytes);
-      else load16_to_lds(bp[j - 8] + k0, bs + (j - 8) * 8 * kSlabBytes);
-    }
+    if (j < 8) load16_to_lds(ap[j] + k0, as + j * 8 * kSlabBytes);
+    else load16_to_lds(bp[j - 8] + k0, as + A_BYTES + (j - 8) * 8 * kSlabBytes);
   };
 
   // ---- L2 prefetch.  The workgroups resident on one XCD at a time form (about) a block of 8 M-tiles
@@ -303,68 +345,73 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
     }
   };
 
-  floatx16 acc[MB][NB];
+  floatx4 acc[MB][NB];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  // ---- fragments: two register sets, k-step s+1 is fetched while k-step s is multiplied
-  const int frow = lane & 31, fhalf = lane >> 5;
+  // ---- fragments.  Operand of a 16x16x32 MFMA: lane l holds row l%16, k = 8*(l/16) .. +7 of the
+  // 32-wide k-step, i.e. 16-byte chunk 4*s + l/16 of its row in the slab.  A k-step is consumed in
+  // two phases (all eight A blocks against B blocks 0..3, then against B blocks 4..7), so the
+  // register sets are: A two sets of eight, B two sets of four.
+  const int frow = lane & 15, fq = lane >> 4;
   const int arow = (wm * WM + frow) * kSlabBytes, brow = A_BYTES + (wn * WN + frow) * kSlabBytes;
-  const int swz = (frow >> 1) & 7;                 // the other row blocks are 32 rows apart: same swizzle
-  uint4 fa[2][MB], fb[2][NB];
-  auto fetch = [&](int set, const unsigned char* stage, int s) __attribute__((always_inline)) {
-    const int slot = ((s * 2 + fhalf) ^ swz) << 4;
-#pragma unroll
-    for (int i = 0; i < MB; ++i) fa[set][i] = *reinterpret_cast<const uint4*>(stage + arow + i * 32 * kSlabBytes + slot);
-#pragma unroll
-    for (int j = 0; j < NB; ++j) fb[set][j] = *reinterpret_cast<const uint4*>(stage + brow + j * 32 * kSlabBytes + slot);
-  };
-  auto mma = [&](int set) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-      for (int j = 0; j < NB; ++j) mma_step<bf16_t>(fa[set][i], fb[set][j], acc[i][j]);
-  };
-  // one k-step = 16 MFMA: the first eight each followed by one fragment read, the next nvmem each
-  // followed by one slab load; a full fence keeps the steps apart
-  auto pin = [&](int nvmem) __attribute__((always_inline)) {
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (q < nvmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  };
+  const int swz = (frow >> 1) & 7;                 // the other row blocks are 16 rows apart: same swizzle
+  u32x4_t fa[2][MB], fb[2][NB / 2];
   auto kof = [&](int k) __attribute__((always_inline)) { return (k < nk ? k : nk - 1) * BK; };   // past the end: harmless re-load
 
-  // slab kt sits in `cur`; on entry fragment set 0 holds its k-step 0 and loads 0..5 of slab kt+1 are
-  // in flight towards `nxt`.
+  // One phase = 32 MFMAs on (fa[aset], fb[bset]) into column half `half`, with, at fixed places between them,
+  //  * fragment reads for the next phase, one per DSG MFMAs.  kind 4: fb[bset^1] <- B blocks 4..7 of
+  //    k-step fs in fstage; kind 12: fa[aset^1], fb[bset^1] <- A blocks 0..7 and B blocks 0..3 of k-step fs
+  //  * slab loads lo .. lo+nvm-1 of the slab at k0 into wstage.
+  // Every MFMA (with what follows it) is fenced off, so the order below is the order issued.
+  auto phase = [&](int aset, int bset, int half, int kind, const unsigned char* fstage, int fs,
+                   int k0, unsigned char* wstage, int lo, int nvm) __attribute__((always_inline)) {
+    const int slot = ((fs * 4 + fq) ^ swz) << 4;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      mfma16(acc[q >> 2][half * 4 + (q & 3)], fa[aset][q >> 2], fb[bset][q & 3]);
+      if (q % DSG == 0 && q / DSG < kind) {
+        const int f = q / DSG;
+        if (kind == 4) fb[bset ^ 1][f] = *reinterpret_cast<const u32x4_t*>(fstage + brow + (4 + f) * 16 * kSlabBytes + slot);
+        else if (f < 8) fa[aset ^ 1][f] = *reinterpret_cast<const u32x4_t*>(fstage + arow + f * 16 * kSlabBytes + slot);
+        else fb[bset ^ 1][f - 8] = *reinterpret_cast<const u32x4_t*>(fstage + brow + (f - 8) * 16 * kSlabBytes + slot);
+      }
+      if (q % VMG == VMO && q / VMG < nvm) issue1(k0, wstage, lo + q / VMG);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // Slab kt sits in `cur`.  On entry fa[0] / fb[0] hold its k-step 0 (A all, B blocks 0..3) and loads
+  // 0..5 of slab kt+1 are in flight towards `nxt`.  The last phase runs from registers after the
+  // workgroup barrier, so it covers the first fragment reads of slab kt+1 and the first loads of kt+2.
   auto slab = [&](unsigned char* cur, unsigned char* nxt, int kt, unsigned& pfslot) __attribute__((always_inline)) {
     prefetch(pfslot, kt);
-    fetch(1, cur, 1); issue(kof(kt + 1), nxt, 6, 11);  mma(0); pin(5);
-    fetch(0, cur, 2); issue(kof(kt + 1), nxt, 11, 16); mma(1); pin(5);
-    fetch(1, cur, 3);                                  mma(0); pin(0);
+    phase(0, 0, 0, 4, cur, 0, kof(kt + 1), nxt, 6, 5);
+    phase(0, 1, 1, 12, cur, 1, kof(kt + 1), nxt, 11, 5);
+    phase(1, 0, 0, 4, cur, 1, 0, nxt, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0): own loads have landed, own fragment reads are done
     __syncthreads();                        // ... and so have everybody else's: `nxt` is complete, `cur` is free
-    issue(kof(kt + 2), cur, 0, 6);
-    fetch(0, nxt, 0);                                  mma(1); pin(6);
+    phase(1, 1, 1, 12, nxt, 0, kof(kt + 2), cur, 0, 6);
   };
 
   if (nk > 0) {
-    issue(0, stage0, 0, 16);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) issue1(0, stage0, j);
     __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
     __syncthreads();
-    issue(kof(1), stage1, 0, 6);
-    fetch(0, stage0, 0);
+#pragma unroll
+    for (int j = 0; j < 6; ++j) issue1(kof(1), stage1, j);
+    {
+      const int slot = (fq ^ swz) << 4;
+#pragma unroll
+      for (int i = 0; i < MB; ++i) fa[0][i] = *reinterpret_cast<const u32x4_t*>(stage0 + arow + i * 16 * kSlabBytes + slot);
+#pragma unroll
+      for (int j = 0; j < NB / 2; ++j) fb[0][j] = *reinterpret_cast<const u32x4_t*>(stage0 + brow + j * 16 * kSlabBytes + slot);
+    }
     for (int kt = 0; kt < nk; kt += 2) {    // nk is even (K % 128 == 0 is a launch condition)
       slab(stage0, stage1, kt, pf0);
       slab(stage1, stage0, kt + 1, pf1);
@@ -372,32 +419,13 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
   }
   __builtin_amdgcn_s_waitcnt(0x0070);       // trailing re-loads must land before the epilogue reuses LDS
   __syncthreads();
+  mfma_drain();
 
   TileCtx c;
   c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
   c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
-  epi.template run<MB, NB, BM, BN, WAVES_M, WAVES_N, true>(acc, c, stage0, d);
+  epi.template run<Layout16, MB, NB, BM, BN, WAVES_M, WAVES_N, true>(acc, c, stage0, d);
   if (PFD > 0 && (pf_sink ^ pf0 ^ pf1) == 0x9E3779B9u && K < 0) epi.keep_alive();   // never true: keeps the prefetch loads
 }
-
-// Reading one accumulator element in an epilogue.  In the hot kernel the 256 accumulators of a lane
-// live in AGPRs; left to itself the compiler copies all of them to VGPRs at loop exit and spills
-// most of them to scratch (tens of GB of extra HBM traffic per launch).  Reading each element
-// through an explicit v_accvgpr_read at its point of use keeps them where they are.
-template <bool AGPR>
-__device__ inline float acc_read(const floatx16& v, int i) {
-  if constexpr (AGPR) {
-    float r;
-    const float e = v[i];
-    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(r) : "a"(e));
-    return r;
-  } else {
-    return v[i];
-  }
-}
-
-// accumulator coordinates inside a wavefront sub-tile
-__device__ inline int acc_row(int bi, int i, int lane) { return bi * 32 + ((i >> 2) << 3) + ((lane >> 5) << 2) + (i & 3); }
-__device__ inline int acc_col(int bj, int lane) { return bj * 32 + (lane & 31); }
 
 }  // namespace rlk

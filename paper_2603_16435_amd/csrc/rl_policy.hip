@@ -33,7 +33,7 @@ constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 
 // sweeps on the 7B-shaped workload at 32768-row chunks: the logits GEMMs like bands of 8 with the
 // prefetch on (261 vs 270 ms per step), dX is best without prefetch (256 vs 280 ms), dW with bands of
 // 4 (270 vs 285 ms); bands of 16 or more lose 5-40 %.
-constexpr int kBandLogits = 8, kPrefetchLogits = 4, kBandDX = 8, kBandDW = 4;
+constexpr int kBandLogits = 8, kPrefetchLogits = 4, kBandDX = 8, kPrefetchDX = 4, kBandDW = 4, kPrefetchDW = 0;
 
 struct Ctrl {            // device control block at the head of the workspace
   int n_real;
@@ -506,8 +506,8 @@ static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, con
   const bool fast = (d.K % 128 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
                     ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
   if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
-  if (pfd > 0) gemm_nt_bf16_kernel<Epi, 4><<<tiles, 256, 0, s>>>(A, B, d, epi);
-  else gemm_nt_bf16_kernel<Epi, 0><<<tiles, 256, 0, s>>>(A, B, d, epi);
+  if (pfd > 0) gemm_nt_bf16_kernel<Epi, 4, 5, 3><<<tiles, 256, 0, s>>>(A, B, d, epi);
+  else gemm_nt_bf16_kernel<Epi, 0, 4, 1><<<tiles, 256, 0, s>>>(A, B, d, epi);
 }
 
 template <class Epi>
@@ -604,7 +604,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = kBandDX;
       EpiDX<T> e{q.row_map, dX, p.H, p.H};
       ProfScope ps(RL_PROF_GEMM_DX, s);
-      launch_gemm(dS, WT, d, e, 0, s);
+      launch_gemm(dS, WT, d, e, kPrefetchDX, s);
     }
     {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
       GemmDims d{};
@@ -612,7 +612,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = kBandDW;
       EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
       ProfScope ps(RL_PROF_GEMM_DW, s);
-      launch_gemm(dST, XT, d, e, 0, s);
+      launch_gemm(dST, XT, d, e, kPrefetchDW, s);
     }
   }
 }
