@@ -20,6 +20,7 @@ template <> __device__ inline float fast_exp<float>(float x) { return expf(x); }
 //      u feeds the entropy H_t = lse_t - u/s of the full distribution at no extra pass.
 template <class T>
 struct EpiFwd {
+  static constexpr bool kPermute = false;
   __device__ void keep_alive() const { zy_c[0] = 0.f; }
   const int* ids_c;     // [chunk-global compact row] sampled token
   float* zy_c;          // [compact row] target logit
@@ -109,8 +110,14 @@ template <> struct Pack4<float> {
 //      f32 (subtraction and scaling before rounding) and stored in the input precision twice:
 //      token-major dS[t][v] (operand of dX = dS W) and vocab-major dST[v][t] (operand of
 //      dW = dS^T X), so that both later contractions have K contiguous.
+//
+//      In the hot kernel (16x16 blocks) the tile rows and columns are relabelled (kPermute, see
+//      perm_row / perm_col in gemm_nt.h) such that a lane ends up holding eight consecutive
+//      vocabulary entries of a token and eight consecutive tokens of a vocabulary entry: both
+//      copies then leave in 16-byte stores, 64 per wavefront and tile, with no staging through LDS.
 template <class T>
 struct EpiDS {
+  static constexpr bool kPermute = true;
   __device__ void keep_alive() const { dS[0] = (T)0.f; }
   const int* ids_c; const float* lse_c; const float* c_c;
   T* dS;  int64_t ld_ds;    // [chunk rows][Vp]
@@ -119,30 +126,76 @@ struct EpiDS {
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+    if constexpr (L::kBlk == 16 && sizeof(T) == 2) {
+      static_assert(MB == 8 && NB == 8, "the relabelling is written for 128x128 wavefront sub-tiles");
+      const int g = c.lane >> 4, cc = c.lane & 15;
+      int y[NB]; float lse[NB], ct[NB];
 #pragma unroll
-    for (int bj = 0; bj < NB; ++bj) {
-      const int n = c.n0 + L::col(bj, c.lane);
-      const bool valid = n < c.Nv;
-      const int g = d.chunk_start + n;
-      const int y = valid ? ids_c[g] : -1;
-      const float lse = valid ? lse_c[g] : 0.f;
-      const float ct = valid ? c_c[g] : 0.f;
+      for (int bj = 0; bj < NB; ++bj) {
+        const int n = c.n0 + perm_col(bj, cc);
+        const bool valid = n < c.Nv;
+        const int t = d.chunk_start + n;
+        y[bj] = valid ? ids_c[t] - c.m0 : -1;             // relative to the sub-tile; -1 never matches
+        lse[bj] = valid ? lse_c[t] : 3.0e38f;             // invalid token: p = exp(z - huge) = 0 and
+        ct[bj] = valid ? c_c[t] : 0.f;                    // c = 0, so every dS entry becomes 0
+      }
+      const int vleft = V - c.m0;                          // sub-tile rows >= vleft are vocabulary padding
 #pragma unroll
-      for (int bi = 0; bi < MB; ++bi)
+      for (int k = 0; k < MB / 2; ++k) {                   // block rows 2k, 2k+1: vocab offsets k*32 + g*8 .. +7
+        const int mrel = k * 32 + g * 8;
+        bf16_t o[NB][8];
 #pragma unroll
-        for (int q = 0; q < L::kRegs / 4; ++q) {
-          const int m = c.m0 + L::row(bi, q * 4, c.lane);
-          float o[4];
+        for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float p = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], q * 4 + e) - lse);
-            const float ds = ct * (((m + e) == y ? 1.f : 0.f) - p);
-            o[e] = (valid && (m + e) < V) ? ds : 0.f;
-          }
-          Pack4<T>::store(dS + (int64_t)n * ld_ds + m, o[0], o[1], o[2], o[3]);
+          for (int bb = 0; bb < 2; ++bb)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) dST[(int64_t)(m + e) * ld_dst + n] = (T)o[e];
+            for (int e = 0; e < 4; ++e) {
+              const int m = mrel + bb * 4 + e;
+              const float pr = fast_exp<T>(acc_read<AGPR>(acc[2 * k + bb][bj], e) - lse[bj]);
+              const float ds = ct[bj] * ((m == y[bj] ? 1.f : 0.f) - pr);
+              o[bj][bb * 4 + e] = (bf16_t)(m < vleft ? ds : 0.f);
+            }
+#pragma unroll
+        for (int bj = 0; bj < NB; ++bj) {
+          bf16x8 v;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[i] = o[bj][i];
+          *reinterpret_cast<bf16x8*>(dS + (int64_t)(c.n0 + perm_col(bj, cc)) * ld_ds + c.m0 + mrel) = v;
         }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          bf16x8 v;
+#pragma unroll
+          for (int bj = 0; bj < NB; ++bj) v[bj] = o[bj][i];
+          *reinterpret_cast<bf16x8*>(dST + (int64_t)(c.m0 + mrel + i) * ld_dst + c.n0 + cc * 8) = v;
+        }
+      }
+    } else {
+#pragma unroll
+      for (int bj = 0; bj < NB; ++bj) {
+        const int n = c.n0 + L::col(bj, c.lane);
+        const bool valid = n < c.Nv;
+        const int g = d.chunk_start + n;
+        const int y = valid ? ids_c[g] : -1;
+        const float lse = valid ? lse_c[g] : 0.f;
+        const float ct = valid ? c_c[g] : 0.f;
+#pragma unroll
+        for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+          for (int q = 0; q < L::kRegs / 4; ++q) {
+            const int m = c.m0 + L::row(bi, q * 4, c.lane);
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float p = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], q * 4 + e) - lse);
+              const float ds = ct * (((m + e) == y ? 1.f : 0.f) - p);
+              o[e] = (valid && (m + e) < V) ? ds : 0.f;
+            }
+            Pack4<T>::store(dS + (int64_t)n * ld_ds + m, o[0], o[1], o[2], o[3]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dST[(int64_t)(m + e) * ld_dst + n] = (T)o[e];
+          }
+      }
     }
   }
 };
@@ -150,6 +203,7 @@ struct EpiDS {
 // ---- backward, stage 2: dX tile -> rows scattered back to their original positions
 template <class T>
 struct EpiDX {
+  static constexpr bool kPermute = false;
   __device__ void keep_alive() const { dX[0] = (T)0.f; }
   const int* row_map;   // compact row -> original row
   T* dX; int64_t ldx; int H;
@@ -174,6 +228,7 @@ struct EpiDX {
 
 // ---- backward, stage 3: dW tile, f32, overwritten by the first chunk and accumulated after
 struct EpiDW {
+  static constexpr bool kPermute = false;
   __device__ void keep_alive() const { dW[0] = 0.f; }
   float* dW; int64_t ldw; int V, H; int accumulate;
 

@@ -250,6 +250,16 @@ __device__ inline void load16_to_lds(const void* g, void* l) {   // 64 lanes x 1
   __builtin_amdgcn_global_load_lds((glb_ptr_t)g, (lds_ptr_t)l, 16, 0, 0);
 }
 
+// Optional relabelling of the tile's rows and columns in the hot kernel (epilogues with kPermute).
+// Which matrix row an LDS row holds is free to choose as long as the epilogue uses the same map.
+// Inside each 128-row half of the tile, LDS row 16*b + 4*g + e (block b, lane group g, register e)
+// holds matrix row 32*(b/2) + 8*g + 4*(b%2) + e, and LDS column-row 16*b + c holds matrix column
+// 8*c + b: a lane (g, c) then owns runs of eight consecutive rows and of eight consecutive columns.
+__device__ inline int perm_row(int b, int g, int e) { return ((b >> 1) << 5) + (g << 3) + ((b & 1) << 2) + e; }
+__device__ inline int perm_col(int b, int c) { return (c << 3) + b; }
+__device__ inline int perm_lds_row_a(int lr) { return (lr & 128) + perm_row((lr >> 4) & 7, (lr >> 2) & 3, lr & 3); }
+__device__ inline int perm_lds_row_b(int lr) { return (lr & 128) + perm_col((lr >> 4) & 7, lr & 15); }
+
 // One 16x16x32 bf16 MFMA, accumulator in place.  Written as inline asm so that the 64 accumulator
 // blocks of a lane are pinned to the 256 AGPRs for the whole kernel: with the builtin the register
 // allocator splits them between the two register files and fills the main loop with copies.  The
@@ -303,10 +313,10 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
   for (int j = 0; j < 8; ++j) {
     const int lr = wave * 64 + j * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((lr >> 1) & 7);
-    int r = tm * BM + lr; r = r < M ? r : M - 1;
+    int r = tm * BM + (Epi::kPermute ? perm_lds_row_a(lr) : lr); r = r < M ? r : M - 1;
     if (d.a_rows) r = d.a_rows[r];
     ap[j] = A + (int64_t)r * d.lda + c * 8;
-    r = tn * BN + lr; r = r < N ? r : N - 1;
+    r = tn * BN + (Epi::kPermute ? perm_lds_row_b(lr) : lr); r = r < N ? r : N - 1;
     if (d.b_rows) r = d.b_rows[r];
     bp[j] = B + (int64_t)r * d.ldb + c * 8;
   }
