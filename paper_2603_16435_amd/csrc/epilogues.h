@@ -15,6 +15,13 @@ template <class T> __device__ inline float fast_exp(float x);
 template <> __device__ inline float fast_exp<bf16_t>(float x) { return __expf(x); }
 template <> __device__ inline float fast_exp<float>(float x) { return expf(x); }
 
+// exp(z - m) with m*log2(e) precomputed: one fma and one v_exp for bf16 inputs, the accurate libm path for f32
+template <class T> __device__ inline float exp_shifted(float z, float m, float m_l2e);
+template <> __device__ inline float exp_shifted<bf16_t>(float z, float, float m_l2e) {
+  return __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.4426950408889634f, -m_l2e));
+}
+template <> __device__ inline float exp_shifted<float>(float z, float m, float) { return expf(z - m); }
+
 // ---- forward: per-token partial (max m, s = sum exp(z-m), u = sum exp(z-m) z) over this tile's vocab
 //      range + target gather; z_t[y_t] is written by the single lane that holds vocab row y_t of token t.
 //      u feeds the entropy H_t = lse_t - u/s of the full distribution at no extra pass.
@@ -28,37 +35,63 @@ struct EpiFwd {
   int ldp;              // = chunk rows
   int V;
 
+  // one token column of one lane: the MB * kRegs logits it holds.  PAD: some of the sub-tile's rows are
+  // vocabulary padding (only in the last tile row) and must not enter the sums.
+  template <class L, int MB, int NB, bool AGPR, bool PAD>
+  __device__ __attribute__((always_inline)) void column(typename L::acc_t (&acc)[MB][NB], int bj, int lane, int vleft,
+                                                        float& mx, float& sm, float& su) const {
+    const float NEG = -__builtin_inff();
+    float z[MB * L::kRegs];
+    mx = NEG;
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+      for (int i = 0; i < L::kRegs; ++i) {
+        const float v = acc_read<AGPR>(acc[bi][bj], i);
+        z[bi * L::kRegs + i] = v;
+        mx = fmaxf(mx, (!PAD || L::row(bi, i, lane) < vleft) ? v : NEG);
+      }
+    const float ms = (mx == NEG) ? 0.f : mx;
+    const float ms_l2e = ms * 1.4426950408889634f;
+    sm = 0.f; su = 0.f;
+#pragma unroll
+    for (int bi = 0; bi < MB; ++bi)
+#pragma unroll
+      for (int i = 0; i < L::kRegs; ++i) {
+        const float v = z[bi * L::kRegs + i];
+        float e = exp_shifted<T>(v, ms, ms_l2e);
+        if (PAD && !(L::row(bi, i, lane) < vleft)) e = 0.f;
+        sm += e;
+        su = __builtin_fmaf(e, v, su);
+      }
+  }
+
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
     float4* red = reinterpret_cast<float4*>(smem);              // [WAVES_M][BN]
     const float NEG = -__builtin_inff();
+    const int vleft = V - c.m0;                                 // rows of this sub-tile below vleft are real vocabulary
+    const bool pad = vleft < MB * L::kBlk;                      // wavefront-uniform
 #pragma unroll
     for (int bj = 0; bj < NB; ++bj) {
       const int n = c.n0 + L::col(bj, c.lane);
       const bool valid = n < c.Nv;
-      const int y = valid ? ids_c[d.chunk_start + n] : -1;
-      float mx = NEG;
+      // target gather: at most one lane of the whole grid holds row y of column n, so this branch is almost never taken
+      const int yrel = valid ? ids_c[d.chunk_start + n] - c.m0 : -1;
+      if (yrel >= 0 && yrel < MB * L::kBlk && L::owns(yrel, c.lane)) {
+        float zy = 0.f;
 #pragma unroll
-      for (int bi = 0; bi < MB; ++bi)
+        for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-        for (int i = 0; i < L::kRegs; ++i) {
-          const int m = c.m0 + L::row(bi, i, c.lane);
-          const float v = acc_read<AGPR>(acc[bi][bj], i);
-          if (m == y) zy_c[d.chunk_start + n] = v;
-          mx = fmaxf(mx, (m < V) ? v : NEG);
-        }
-      const float ms = (mx == NEG) ? 0.f : mx;
-      float sm = 0.f, su = 0.f;
-#pragma unroll
-      for (int bi = 0; bi < MB; ++bi)
-#pragma unroll
-        for (int i = 0; i < L::kRegs; ++i) {
-          const int m = c.m0 + L::row(bi, i, c.lane);
-          const float z = acc_read<AGPR>(acc[bi][bj], i);
-          const float e = (m < V) ? fast_exp<T>(z - ms) : 0.f;
-          sm += e;
-          su += (m < V) ? e * z : 0.f;
-        }
+          for (int i = 0; i < L::kRegs; ++i) {
+            const float v = acc_read<AGPR>(acc[bi][bj], i);
+            if (L::row(bi, i, c.lane) == yrel) zy = v;
+          }
+        zy_c[d.chunk_start + n] = zy;
+      }
+      float mx, sm, su;
+      if (pad) column<L, MB, NB, AGPR, true>(acc, bj, c.lane, vleft, mx, sm, su);
+      else column<L, MB, NB, AGPR, false>(acc, bj, c.lane, vleft, mx, sm, su);
       // merge with the lane groups that hold the other rows of this column
 #pragma unroll
       for (int off = L::kBlk; off < 64; off <<= 1) {
@@ -129,7 +162,7 @@ struct EpiDS {
     if constexpr (L::kBlk == 16 && sizeof(T) == 2) {
       static_assert(MB == 8 && NB == 8, "the relabelling is written for 128x128 wavefront sub-tiles");
       const int g = c.lane >> 4, cc = c.lane & 15;
-      int y[NB]; float lse[NB], ct[NB];
+      int y[NB]; float lse[NB], lse_l2e[NB], ct[NB];
 #pragma unroll
       for (int bj = 0; bj < NB; ++bj) {
         const int n = c.n0 + perm_col(bj, cc);
@@ -138,6 +171,7 @@ struct EpiDS {
         y[bj] = valid ? ids_c[t] - c.m0 : -1;             // relative to the sub-tile; -1 never matches
         lse[bj] = valid ? lse_c[t] : 3.0e38f;             // invalid token: p = exp(z - huge) = 0 and
         ct[bj] = valid ? c_c[t] : 0.f;                    // c = 0, so every dS entry becomes 0
+        lse_l2e[bj] = lse[bj] * 1.4426950408889634f;
       }
       const int vleft = V - c.m0;                          // sub-tile rows >= vleft are vocabulary padding
 #pragma unroll
@@ -151,7 +185,7 @@ struct EpiDS {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const int m = mrel + bb * 4 + e;
-              const float pr = fast_exp<T>(acc_read<AGPR>(acc[2 * k + bb][bj], e) - lse[bj]);
+              const float pr = exp_shifted<T>(acc_read<AGPR>(acc[2 * k + bb][bj], e), lse[bj], lse_l2e[bj]);
               const float ds = ct[bj] * ((m == y[bj] ? 1.f : 0.f) - pr);
               o[bj][bb * 4 + e] = (bf16_t)(m < vleft ? ds : 0.f);
             }

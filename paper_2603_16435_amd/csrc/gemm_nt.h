@@ -110,12 +110,14 @@ struct Layout32 {   // 32x32 MFMA blocks, 16 registers per block: row = 8*(i/4) 
   static constexpr int kBlk = 32, kRegs = 16;
   __device__ static int row(int bi, int i, int lane) { return bi * 32 + ((i >> 2) << 3) + ((lane >> 5) << 2) + (i & 3); }
   __device__ static int col(int bj, int lane) { return bj * 32 + (lane & 31); }
+  __device__ static bool owns(int r, int lane) { return ((r >> 2) & 1) == (lane >> 5); }   // does this lane hold row r of its columns?
 };
 struct Layout16 {   // 16x16 MFMA blocks, 4 registers per block: row = 4*(l/16) + i, col = l%16
   typedef floatx4 acc_t;
   static constexpr int kBlk = 16, kRegs = 4;
   __device__ static int row(int bi, int i, int lane) { return bi * 16 + ((lane >> 4) << 2) + i; }
   __device__ static int col(int bj, int lane) { return bj * 16 + (lane & 15); }
+  __device__ static bool owns(int r, int lane) { return ((r >> 2) & 3) == (lane >> 4); }
 };
 
 // Reading one accumulator element in an epilogue.  In the hot kernel the 256 accumulators of a lane
