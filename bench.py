@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--objective", default="grpo", choices=["grpo", "flow"])
     ap.add_argument("--layout", default="padded", choices=["padded", "packed"])
     ap.add_argument("--chunk-rows", type=int, default=0)
+    ap.add_argument("--backward", default="auto", choices=["auto", "recompute", "stash"],
+                    help="backward mode of the library; auto = single-pass (stash) with max_seq_len = the config's longest response")
     ap.add_argument("--len-div", type=int, default=1, help="shorten every sequence (debug / profiling runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -89,7 +91,8 @@ def main():
     obj = binding.OBJECTIVES[a.objective]
     batch = binding.make_batch(b.hidden, b.weight, b.token_ids, b.mask, b.cu_seqlens, b.group_idx, b.rewards,
                                b.old_logprob, b.ref_logprob, b.log_z, cfg.P)
-    prm = binding.make_params(cfg.clip_eps, cfg.kl_coef, cfg.beta, cfg.adv_eps, cfg.adv_std_ddof, a.chunk_rows)
+    prm = binding.make_params(cfg.clip_eps, cfg.kl_coef, cfg.beta, cfg.adv_eps, cfg.adv_std_ddof, a.chunk_rows,
+                              backward_mode=a.backward, max_seq_len=int(b.lengths.max()))
     plan = binding.PolicyLossPlan(batch, prm, dev, b.hidden.dtype, backward=True)
 
     for _ in range(a.warmup):
@@ -143,7 +146,7 @@ def main():
                                f"{cfg.dtype}, {a.layout} rows R={b.R}, real tokens T={T}, objective={a.objective}"
                                + (f", len_div={a.len_div}" if a.len_div != 1 else ""),
                    "objective": a.objective, "layout": a.layout, "T": T, "R": b.R, "H": cfg.H, "V": cfg.V,
-                   "chunk_rows": a.chunk_rows or binding.lib().rl_default_chunk_rows()},
+                   "chunk_rows": a.chunk_rows or binding.lib().rl_default_chunk_rows(), "backward": a.backward},
         "mfma_frac_6THV": 6.0 * thv / (dt / a.steps) / 1e12 / peak,
         "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
         "roofline": {"bound": "mfma", "kernel": f"gemm_nt_bf16_kernel ({dom})", "achieved": achieved, "peak": peak,

@@ -51,13 +51,29 @@ typedef enum rl_status {
   RL_ERR_NULL = 1,        /* a required pointer is NULL                         */
   RL_ERR_SHAPE = 2,       /* a size is non-positive, too large or misaligned    */
   RL_ERR_DTYPE = 3,       /* unknown rl_dtype                                   */
-  RL_ERR_RANGE = 4,       /* objective / clip_eps / ddof out of range           */
+  RL_ERR_RANGE = 4,       /* objective / clip_eps / ddof / backward mode out of range */
   RL_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than needed  */
   RL_ERR_HIP = 6          /* a HIP launch failed (see hipGetLastError)          */
 } rl_status;
 
 typedef enum rl_objective { RL_OBJ_GRPO = 0, RL_OBJ_FLOW = 1 } rl_objective;
 typedef enum rl_dtype { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
+
+/* How the backward pass gets the probabilities of a chunk of rows.
+ *  RL_BWD_RECOMPUTE  recompute the logits tile by tile from X and W (four contractions per chunk:
+ *                    forward, recompute + dS, dX, dW).  Always available.
+ *  RL_BWD_STASH      single pass: chunks are made of whole sequences, the forward contraction also
+ *                    stores the chunk's unnormalised probabilities exp(z - ref_t) in the input
+ *                    precision (ref_t = target logit - old log-prob, i.e. the row's logsumexp up to
+ *                    the drift between old and current policy), and dX / dW are contracted from
+ *                    that store (three contractions per chunk, the 6 T H V flops the path needs).
+ *                    Needs bf16 inputs, H a multiple of 128, 16-byte aligned hidden / weight and
+ *                    0 < params->max_seq_len <= chunk rows; otherwise RL_ERR_RANGE.  Assumes
+ *                    |old_logprob - current log-prob| stays far below 80 nats (the stored
+ *                    probabilities overflow beyond that and the loss comes back non-finite).
+ *  RL_BWD_AUTO       RL_BWD_STASH when its conditions hold, else RL_BWD_RECOMPUTE.
+ * Either way at most chunk_rows x V values are held at a time, never T x V. */
+typedef enum rl_backward_mode { RL_BWD_AUTO = 0, RL_BWD_RECOMPUTE = 1, RL_BWD_STASH = 2 } rl_backward_mode;
 
 typedef struct rl_batch {
   int64_t R;                    /* rows (tokens incl. masked ones), 1 <= R < 2^31 - 2^16 */
@@ -84,6 +100,9 @@ typedef struct rl_params {
   int32_t adv_std_ddof;         /* 0 (population std) or 1                               */
   int32_t chunk_rows;           /* rows of dS staged at once; 0 = library default.       */
                                 /* rounded up to a multiple of 256; sizes the workspace  */
+  int32_t backward_mode;        /* rl_backward_mode; 0 = RL_BWD_AUTO                     */
+  int32_t max_seq_len;          /* promise: no sequence has more counting rows than this; */
+                                /* 0 = no promise.  Needed by the single-pass backward.   */
 } rl_params;
 
 typedef struct rl_stats {       /* device struct written by the loss call                */
@@ -93,7 +112,8 @@ typedef struct rl_stats {       /* device struct written by the loss call       
   int32_t n_bad_token;          /* mask=1 rows dropped because token id was out of range */
   int32_t n_bad_group;          /* sequences dropped because group_idx was out of range  */
   int32_t n_bad_seq;            /* sequences treated as empty (cu_seqlens decreasing / out of [0,R]) */
-  int32_t reserved[2];
+  int32_t n_seq_too_long;       /* sequences longer than params->max_seq_len (single-pass backward): loss is then NaN */
+  int32_t reserved[1];
 } rl_stats;
 
 typedef struct rl_outputs {     /* NULL = not wanted, except loss                        */
@@ -112,7 +132,8 @@ typedef struct rl_outputs {     /* NULL = not wanted, except loss               
 } rl_outputs;
 
 /* Bytes of device workspace the two calls below need for this batch shape (host only; reads
- * R, H, V, B, P, dtype and params->chunk_rows; params may be NULL = defaults; want_backward
+ * R, H, V, B, P, dtype, the alignment of hidden / weight, and params->chunk_rows, backward_mode,
+ * max_seq_len; params may be NULL = defaults; want_backward
  * = 0 sizes it for rl_token_logprob / loss-only calls).  The workspace must be 256-byte
  * aligned.  Its contents on entry are irrelevant and on return unspecified. */
 rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params,

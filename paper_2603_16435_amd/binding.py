@@ -30,13 +30,14 @@ class rl_batch(C.Structure):
 
 class rl_params(C.Structure):
     _fields_ = [("clip_eps", C.c_float), ("kl_coef", C.c_float), ("beta", C.c_float), ("adv_eps", C.c_float),
-                ("adv_std_ddof", C.c_int32), ("chunk_rows", C.c_int32)]
+                ("adv_std_ddof", C.c_int32), ("chunk_rows", C.c_int32),
+                ("backward_mode", C.c_int32), ("max_seq_len", C.c_int32)]
 
 
 class rl_stats(C.Structure):
     _fields_ = [("n_tokens", C.c_int32), ("n_clip_hi", C.c_int32), ("n_clip_lo", C.c_int32),
                 ("n_bad_token", C.c_int32), ("n_bad_group", C.c_int32), ("n_bad_seq", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("n_seq_too_long", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class rl_outputs(C.Structure):
@@ -53,7 +54,8 @@ class rl_profile(C.Structure):
     _fields_ = [("ms", C.c_double * 8), ("launches", C.c_int64 * 8)]
 
 
-STATS_FIELDS = ("n_tokens", "n_clip_hi", "n_clip_lo", "n_bad_token", "n_bad_group", "n_bad_seq")
+STATS_FIELDS = ("n_tokens", "n_clip_hi", "n_clip_lo", "n_bad_token", "n_bad_group", "n_bad_seq", "n_seq_too_long")
+BACKWARD_MODES = {"auto": 0, "recompute": 1, "stash": 2}
 
 _lib = None
 
@@ -231,18 +233,20 @@ class PolicyLossPlan:
         return self.res
 
 
-def make_params(clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0, chunk_rows=0) -> rl_params:
-    return rl_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows)
+def make_params(clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0, chunk_rows=0,
+                backward_mode="auto", max_seq_len=0) -> rl_params:
+    mode = BACKWARD_MODES[backward_mode] if isinstance(backward_mode, str) else int(backward_mode)
+    return rl_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, mode, int(max_seq_len))
 
 
 def rl_policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards,
                            old_logprob, ref_logprob, log_z=None, P: Optional[int] = None,
                            clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
-                           chunk_rows=0, backward=True) -> LossResult:
+                           chunk_rows=0, backward=True, backward_mode="auto", max_seq_len=0) -> LossResult:
     """One pass of the whole path.  `objective` is "grpo" | "flow" (or the enum value)."""
     obj = OBJECTIVES[objective] if isinstance(objective, str) else int(objective)
     b = make_batch(hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards, old_logprob, ref_logprob, log_z, P)
-    prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows)
+    prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, backward_mode, max_seq_len)
     plan = PolicyLossPlan(b, prm, hidden.device, hidden.dtype, backward)
     return plan.run(obj)
 

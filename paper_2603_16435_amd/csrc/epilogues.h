@@ -126,6 +126,97 @@ struct EpiFwd {
   }
 };
 
+// ---- forward that also keeps the chunk's unnormalised probabilities for a single-pass backward.
+//      Every token has a reference ref_t close to its logsumexp, known before the contraction
+//      (target logit minus the old policy's log-prob), so e = exp(z - ref_t) needs no running
+//      maximum: the epilogue adds up s = sum e and u = sum e z per token and tile row, and
+//      stores e itself in the input precision, token-major E[t][v] and vocab-major ET[v][t] (16-byte
+//      stores through the same relabelling as EpiDS).  bf16 keeps f32's exponent range, so e is
+//      stored at full relative precision whatever its size.  Later, with Z_t = sum_v e,
+//      dS[t][v] = -(c_t / Z_t) (E[t][v] - Z_t 1[v = y_t]): the backward contractions run on E
+//      directly, with the target entry patched and the factor applied per token.
+template <class T>
+struct EpiFwdStash {
+  static constexpr bool kPermute = true;
+  __device__ void keep_alive() const { E[0] = (T)0.f; }
+  const float* ref_l2e;   // [compact row] ref_t * log2(e)
+  float2* part;           // [tiles_m(V)][ldp] partial (s, u) per token of the chunk
+  int ldp;
+  T* E;  int64_t ld_e;    // [chunk rows][Vp]
+  T* ET; int64_t ld_et;   // [Vp][chunk rows]
+  int V;
+
+  // exponentials, sums and the two stores for block rows 2k, 2k+1 (k = 0..3), eight token columns each
+  template <class L, int MB, int NB, bool AGPR, bool PAD>
+  __device__ __attribute__((always_inline)) void body(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, int g, int cc, int vleft,
+                                                      const float (&rl)[NB], float (&sm)[NB], float (&su)[NB]) const {
+#pragma unroll
+    for (int k = 0; k < MB / 2; ++k) {
+      const int mrel = k * 32 + g * 8;
+      bf16x2 et[8][NB / 2];                               // [vocab entry i][token pair]: the transposed copy, packed
+#pragma unroll
+      for (int bj = 0; bj < NB; ++bj) {
+        float ev[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float z = acc_read<AGPR>(acc[2 * k + (i >> 2)][bj], i & 3);
+          float v = __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.4426950408889634f, -rl[bj]));
+          if (PAD && !(mrel + i < vleft)) v = 0.f;
+          sm[bj] += v;
+          su[bj] = __builtin_fmaf(v, z, su[bj]);
+          ev[i] = v;
+          et[i][bj >> 1][bj & 1] = (bf16_t)v;
+        }
+        bf16x8 row;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) row[i] = (bf16_t)ev[i];
+        *reinterpret_cast<bf16x8*>(E + (int64_t)(c.n0 + perm_col(bj, cc)) * ld_e + c.m0 + mrel) = row;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        bf16x8 col;
+#pragma unroll
+        for (int bj = 0; bj < NB; ++bj) col[bj] = et[i][bj >> 1][bj & 1];
+        *reinterpret_cast<bf16x8*>(ET + (int64_t)(c.m0 + mrel + i) * ld_et + c.n0 + cc * 8) = col;
+      }
+      __builtin_amdgcn_sched_barrier(0);                  // keep the four rounds apart: 64 live values each is plenty
+    }
+  }
+
+  template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
+    static_assert(L::kBlk == 16 && MB == 8 && NB == 8 && sizeof(T) == 2, "hot kernel only");
+    float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
+    const int g = c.lane >> 4, cc = c.lane & 15;
+    float rl[NB], sm[NB], su[NB];
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj) {
+      const int n = c.n0 + perm_col(bj, cc);
+      rl[bj] = (n < c.Nv) ? ref_l2e[d.chunk_start + n] : __builtin_inff();   // column without a token: e = exp2(-inf) = 0
+      sm[bj] = 0.f; su[bj] = 0.f;
+    }
+    const int vleft = V - c.m0;                            // sub-tile rows >= vleft are vocabulary padding
+    if (vleft < MB * L::kBlk) body<L, MB, NB, AGPR, true>(acc, c, g, cc, vleft, rl, sm, su);   // wavefront-uniform
+    else body<L, MB, NB, AGPR, false>(acc, c, g, cc, vleft, rl, sm, su);
+#pragma unroll
+    for (int bj = 0; bj < NB; ++bj) {
+#pragma unroll
+      for (int off = 16; off < 64; off <<= 1) { sm[bj] += __shfl_xor(sm[bj], off); su[bj] += __shfl_xor(su[bj], off); }
+      if (c.lane < 16) red[c.wm * BN + c.wn * (BN / WAVES_N) + perm_col(bj, cc)] = make_float2(sm[bj], su[bj]);
+    }
+    __syncthreads();
+    if (c.tid < BN) {
+      const int n = c.tile_n * BN + c.tid;
+      if (n < c.Nv) {
+        float2 r = red[c.tid];
+#pragma unroll
+        for (int w = 1; w < WAVES_M; ++w) { const float2 o2 = red[w * BN + c.tid]; r.x += o2.x; r.y += o2.y; }
+        part[(int64_t)c.tile_m * ldp + n] = r;
+      }
+    }
+  }
+};
+
 template <class T> struct Pack4;
 template <> struct Pack4<bf16_t> {
   __device__ static void store(bf16_t* p, float a, float b, float c, float d) {
@@ -241,6 +332,7 @@ struct EpiDX {
   __device__ void keep_alive() const { dX[0] = (T)0.f; }
   const int* row_map;   // compact row -> original row
   T* dX; int64_t ldx; int H;
+  const float* row_scale;   // optional [chunk row]: factor applied to the whole row
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
@@ -251,10 +343,11 @@ struct EpiDX {
         const int m = c.m0 + L::row(bi, i, c.lane);
         if (m >= c.Mv) continue;
         const int64_t dst = row_map[d.chunk_start + m];
+        const float f = row_scale ? row_scale[m] : 1.f;
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj) {
           const int n = c.n0 + L::col(bj, c.lane);
-          if (n < H) dX[dst * ldx + n] = (T)acc_read<AGPR>(acc[bi][bj], i);
+          if (n < H) dX[dst * ldx + n] = (T)(f * acc_read<AGPR>(acc[bi][bj], i));
         }
       }
   }

@@ -34,6 +34,7 @@ namespace rlk {
 typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -52,9 +53,34 @@ struct GemmDims {
   const int* b_rows;
   const int* n_real;      // device scalar: number of compacted rows in the whole batch
   int chunk_start;        // first compacted row of this chunk
-  int dyn;                // which extent is min(max(*n_real - chunk_start,0), bound): 0 none, 1 M, 2 N, 3 K (rounded up to 256)
+  const int* chunk;       // if set, device pair {first compacted row, rows} of this chunk; replaces n_real / chunk_start,
+                          // and the gather tables are then indexed from the chunk's first row
+  int dyn;                // which extent is min(rows left in the chunk, bound): 0 none, 1 M, 2 N, 3 K (rounded up to 256)
+  int zero_if_empty;      // dyn == 3 only: an empty chunk still runs the epilogue (with K = 0) instead of returning
   int group_m;            // tile-order parameter: M-tiles per band
 };
+
+// Apply the dynamic extent.  Returns false if this launch has nothing to do.
+__device__ inline bool resolve_dims(GemmDims& d, int& M, int& N, int& K) {
+  M = d.M; N = d.N; K = d.K;
+  if (!d.dyn) return true;
+  int left;
+  if (d.chunk) {
+    const int cs = d.chunk[0];
+    left = d.chunk[1];
+    d.chunk_start = cs;
+    if (d.a_rows) d.a_rows += cs;
+    if (d.b_rows) d.b_rows += cs;
+  } else {
+    left = *d.n_real - d.chunk_start;
+  }
+  if (left <= 0) {
+    if (d.dyn == 3 && d.zero_if_empty) K = 0; else return false;
+  } else if (d.dyn == 1) M = left < M ? left : M;
+  else if (d.dyn == 2) N = left < N ? left : N;
+  else { const int k = (left + 255) & ~255; K = k < K ? k : K; }
+  return true;
+}
 
 // Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin, and each XCD has its own
 // L2, so ids are first regrouped such that one XCD receives a contiguous run of tile numbers;
@@ -151,16 +177,8 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-  int M = d.M, N = d.N, K = d.K;
-  if (d.dyn) {
-    const int left = *d.n_real - d.chunk_start;
-    if (left <= 0) {
-      // nothing left for this chunk; the very first K-trimmed launch still has to produce zeros
-      if (d.dyn == 3 && d.chunk_start == 0) K = 0; else return;
-    } else if (d.dyn == 1) M = left < M ? left : M;
-    else if (d.dyn == 2) N = left < N ? left : N;
-    else { const int k = (left + 255) & ~255; K = k < K ? k : K; }
-  }
+  int M, N, K;
+  if (!resolve_dims(d, M, N, K)) return;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   int tm, tn;
   tile_of_block(blockIdx.x, tiles_m, tiles_n, d.group_m, tm, tn);
@@ -287,15 +305,8 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
   __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
   __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
 
-  int M = d.M, N = d.N, K = d.K;
-  if (d.dyn) {
-    const int left = *d.n_real - d.chunk_start;
-    if (left <= 0) {
-      if (d.dyn == 3 && d.chunk_start == 0) K = 0; else return;
-    } else if (d.dyn == 1) M = left < M ? left : M;
-    else if (d.dyn == 2) N = left < N ? left : N;
-    else { const int k = (left + 255) & ~255; K = k < K ? k : K; }
-  }
+  int M, N, K;
+  if (!resolve_dims(d, M, N, K)) return;
   const int nk = K / BK;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   int tm, tn;

@@ -29,15 +29,22 @@ constexpr int kDefaultChunkRows = 32768;
 constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
 constexpr int kGemmThreads = kWavesM * kWavesN * 64;
 constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 KiB per CU
-// Tile-order band height (M-tiles per band) and L2 prefetch of the hot kernel, per contraction, from
-// sweeps on the 7B-shaped workload at 32768-row chunks: the logits GEMMs like bands of 8 with the
-// prefetch on (261 vs 270 ms per step), dX is best without prefetch (256 vs 280 ms), dW with bands of
-// 4 (270 vs 285 ms); bands of 16 or more lose 5-40 %.
-constexpr int kBandLogits = 8, kPrefetchLogits = 4, kBandDX = 8, kPrefetchDX = 4, kBandDW = 4, kPrefetchDW = 0;
+// Per-contraction tuning of the hot kernel, from sweeps on the 7B-shaped workload at 32768-row chunks:
+// tile-order band height (M-tiles per band), L2 prefetch distance in slabs (0 = off) and where in a
+// phase of 32 MFMAs the slab loads are issued (after MFMA kVmo, kVmo + kVmg, ...).
+struct TuneLogits { static constexpr int kBand = 8, kPfd = 4, kVmg = 5, kVmo = 3; };
+struct TuneDX     { static constexpr int kBand = 8, kPfd = 2, kVmg = 5, kVmo = 3; };
+struct TuneDW     { static constexpr int kBand = 4, kPfd = 2, kVmg = 4, kVmo = 1; };
 
 struct Ctrl {            // device control block at the head of the workspace
   int n_real;
-  int pad[15];
+  int too_long;          // single-pass backward: some sequence has more rows than the caller promised / a chunk holds
+  int pad[14];
+};
+
+struct ChunkDesc {       // device record of one sequence-aligned chunk (single-pass backward)
+  int row_start, rows;   // compacted rows [row_start, row_start + rows)
+  int seq_begin, seq_end;// sequences [seq_begin, seq_end) lie wholly inside
 };
 
 // ------------------------------------------------------------------ optional launch timing
@@ -158,6 +165,7 @@ __global__ void seq_scan_kernel(const int32_t* seq_len, int B, int32_t* cstart, 
   if (threadIdx.x == 0) {
     cstart[B] = carry;
     ctrl->n_real = carry;
+    ctrl->too_long = 0;
     if (stats) stats->n_tokens = carry;
   }
 }
@@ -226,6 +234,100 @@ __global__ void advantage_kernel(const float* rewards, const int32_t* group_idx,
   for (int i = 0; i < B; ++i) if (group_idx[i] == p) adv[i] = (float)(((double)rewards[i] - mu) * inv);
 }
 
+// ------------------------------------------------------------------ single-pass backward: chunking and references
+// Greedy packing of whole sequences into chunks of at most Tc compacted rows (one thread: B is small).
+// Two consecutive chunks together hold more than Tc rows, so n_desc = 2 ceil(R / Tc) + 1 records
+// always suffice; unused records are empty.  A sequence longer than max_len (<= Tc) raises the flag.
+__global__ void chunk_build_kernel(const int32_t* seq_len, const int32_t* cstart, int B, int Tc, int max_len,
+                                   ChunkDesc* desc, int n_desc, Ctrl* ctrl, rl_stats* stats) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int k = 0, start = 0, rows = 0, sb = 0, bad = 0;
+  for (int i = 0; i < B; ++i) {
+    const int n = seq_len[i];
+    if (n > max_len) ++bad;
+    if (rows > 0 && rows + n > Tc && k < n_desc - 1) {
+      desc[k].row_start = start; desc[k].rows = rows; desc[k].seq_begin = sb; desc[k].seq_end = i;
+      ++k; start += rows; rows = 0; sb = i;
+    }
+    rows += n;
+  }
+  desc[k].row_start = start; desc[k].rows = rows; desc[k].seq_begin = sb; desc[k].seq_end = B;
+  for (int j = k + 1; j < n_desc; ++j) { desc[j].row_start = start + rows; desc[j].rows = 0; desc[j].seq_begin = B; desc[j].seq_end = B; }
+  if (bad) { ctrl->too_long = 1; if (stats) stats->n_seq_too_long = bad; }
+}
+
+// One wavefront per compacted row t: target logit zy_t = x_t . W[y_t] (f32 accumulation of bf16 products)
+// and the reference of the stored probabilities, ref_t = zy_t - old_t, which is the logsumexp of the
+// row up to the (small) drift between the old and the current policy.
+__global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, const int32_t* row_map, const int32_t* ids_c,
+                                    const float* old_lp, const Ctrl* ctrl, float* zy, float* ref_l2e) {
+  const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= ctrl->n_real) return;
+  const int lane = threadIdx.x & 63;
+  const int r = row_map[t];
+  const uint4* x = reinterpret_cast<const uint4*>(X + (int64_t)r * H);
+  const uint4* w = reinterpret_cast<const uint4*>(W + (int64_t)ids_c[t] * H);
+  float acc = 0.f;
+  for (int k = lane; k < H / 8; k += 64) {
+    const uint4 a = x[k], b = w[k];
+    const unsigned av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc = fmaf(__uint_as_float(av[j] << 16), __uint_as_float(bv[j] << 16), acc);
+      acc = fmaf(__uint_as_float(av[j] & 0xffff0000u), __uint_as_float(bv[j] & 0xffff0000u), acc);
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o);
+  if (lane == 0) { zy[t] = acc; ref_l2e[t] = (acc - old_lp[r]) * 1.4426950408889634f; }
+}
+
+// Per-tile-row partial sums (s, u) of a chunk -> lse, logp, entropy and Z_t = sum_v exp(z - ref_t).
+// A workgroup handles 64 rows x 4 slices of the tile range, merged through LDS in a fixed order.
+__global__ void lse_sum_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c, const float* ref_l2e,
+                               const int32_t* row_map, const ChunkDesc* desc,
+                               float* lse_c, float* logp_c, float* zsum_c, float* lse_out, float* logp_out, float* ent_out) {
+  __shared__ double ss[4][64], su[4][64];
+  const int left = desc->rows, chunk_start = desc->row_start;
+  if ((int)blockIdx.x * 64 >= left) return;
+  const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + col;
+  double s = 0.0, u = 0.0;
+  if (n < left)
+    for (int t = slice; t < tiles_v; t += 4) { const float2 v = part[(int64_t)t * ldp + n]; s += (double)v.x; u += (double)v.y; }
+  ss[slice][col] = s; su[slice][col] = u;
+  __syncthreads();
+  if (slice == 0 && n < left) {
+    const double S = ss[0][col] + ss[1][col] + ss[2][col] + ss[3][col];
+    const double U = su[0][col] + su[1][col] + su[2][col] + su[3][col];
+    const int g = chunk_start + n;
+    const double lse_d = (double)ref_l2e[g] * 0.6931471805599453 + log(S);
+    const float lse = (float)lse_d;
+    const float lp = zy_c[g] - lse;
+    lse_c[g] = lse; logp_c[g] = lp; zsum_c[g] = (float)S;
+    const int r = row_map[g];
+    if (lse_out) lse_out[r] = lse;
+    if (logp_out) logp_out[r] = lp;
+    if (ent_out) ent_out[r] = (float)fmax(lse_d - U / S, 0.0);
+  }
+}
+
+// After the loss: per row of the chunk the factor -c_t / Z_t of the backward contractions, and the
+// target entry of the stored probabilities replaced by e_y - Z_t (so that -c/Z times the stored row is dS).
+template <class T>
+__global__ void stash_patch_kernel(const ChunkDesc* desc, const int32_t* ids_c, const float* zy_c, const float* ref_l2e,
+                                   const float* zsum_c, const float* c_c, float* row_scale, T* E, int64_t ld_e, T* ET, int64_t ld_et) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= desc->rows) return;
+  const int g = desc->row_start + n;
+  const float Z = zsum_c[g];
+  row_scale[n] = -c_c[g] / Z;
+  const float ey = exp2f(fmaf(zy_c[g], 1.4426950408889634f, -ref_l2e[g]));
+  const T v = (T)(ey - Z);
+  const int y = ids_c[g];
+  E[(int64_t)n * ld_e + y] = v;
+  ET[(int64_t)y * ld_et + n] = v;
+}
+
 // ------------------------------------------------------------------ forward combine
 // Fold the per-vocab-tile partials (max, sumexp) of a chunk into lse, logp.  A workgroup handles 64
 // compact rows x 4 slices of the tile range: one online (rescaling) pass per thread, coalesced
@@ -282,10 +384,15 @@ __global__ void seq_loss_kernel(int objective, const float* logp_c, const float*
                                 const int32_t* row_map, const int32_t* cstart, const float* adv,
                                 const int32_t* group_idx, const float* log_z, int B,
                                 float clip_eps, float kl_coef, float beta,
-                                float* seq_loss, float* gterm, float* c_c, float* coeff_out, rl_stats* stats) {
+                                float* seq_loss, float* gterm, float* c_c, float* coeff_out, rl_stats* stats,
+                                const ChunkDesc* desc) {
   __shared__ double sh[16];
   __shared__ int sh_hi, sh_lo;
-  const int i = blockIdx.x;
+  int i = blockIdx.x;
+  if (desc) {                           // only the sequences of one chunk
+    i += desc->seq_begin;
+    if (i >= desc->seq_end) return;
+  }
   const int a = cstart[i], b = cstart[i + 1], n = b - a;
   if (threadIdx.x == 0) { sh_hi = 0; sh_lo = 0; }
   if (n <= 0) {
@@ -352,7 +459,7 @@ __global__ void seq_loss_kernel(int objective, const float* logp_c, const float*
 
 // loss = (1/B) sum_i seq_loss_i ;  d_logZ_p = sum over members of gterm  (single workgroup)
 __global__ void finalize_kernel(const float* seq_loss, const float* gterm, const int32_t* group_idx,
-                                const int32_t* seq_len, int B, int P, int objective,
+                                const int32_t* seq_len, int B, int P, int objective, const Ctrl* ctrl,
                                 float* loss, float* d_log_z, float* seq_loss_out) {
   __shared__ double sh[16];
   double acc = 0.0;
@@ -361,7 +468,8 @@ __global__ void finalize_kernel(const float* seq_loss, const float* gterm, const
     if (seq_loss_out) seq_loss_out[i] = seq_loss[i];
   }
   const double tot = block_sum(acc, sh);
-  if (threadIdx.x == 0) *loss = (float)(tot / B);
+  // a sequence longer than the caller promised: the single-pass backward dropped rows, say so loudly
+  if (threadIdx.x == 0) *loss = ctrl->too_long ? __builtin_nanf("") : (float)(tot / B);
   if (d_log_z) {
     for (int p = threadIdx.x; p < P; p += blockDim.x) {
       double s = 0.0;
@@ -376,12 +484,13 @@ __global__ void finalize_kernel(const float* seq_loss, const float* gterm, const
 // dst[c][r] = src[row_of(r)][c] for r < rows_valid, 0 for rows_valid <= r < ld_dst rows covered by the grid.
 template <class T>
 __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int cols, const int32_t* row_idx,
-                                 const Ctrl* ctrl, int chunk_start, int dyn_rows,
+                                 const Ctrl* ctrl, int chunk_start, int dyn_rows, const ChunkDesc* desc, const float* row_scale,
                                  T* dst, int64_t ld_dst, int rows_padded) {
   __shared__ T tile[64][65];
   int rv = rows;
   if (dyn_rows) {
-    int left = ctrl->n_real - chunk_start;
+    int left;
+    if (desc) { chunk_start = desc->row_start; left = desc->rows; } else left = ctrl->n_real - chunk_start;
     if (left <= 0) return;
     rv = left < rows ? left : rows;
   }
@@ -394,6 +503,7 @@ __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int col
     if (r < rv && c < cols) {
       const int64_t sr = row_idx ? (int64_t)row_idx[chunk_start + r] : (int64_t)r;
       v = src[sr * ld_src + c];
+      if (row_scale) v = (T)((float)v * row_scale[r]);
     }
     tile[k][tx] = v;
   }
@@ -442,8 +552,11 @@ struct Plan {
   int64_t R; int H, V, B, P; int dtype; size_t esz;
   int Tc, Vp, tiles_v, n_chunks;
   bool bwd;
+  bool stash;            // single-pass backward (forward keeps each chunk's unnormalised probabilities)
+  int n_desc, max_len;   // stash: number of chunk records, promised bound on rows per sequence
   size_t off_ctrl, off_seq_len, off_cstart, off_row_map, off_ids_c, off_cpos, off_zy, off_lse_c, off_logp_c,
-      off_c_c, off_adv, off_seq_loss, off_gterm, off_part, off_wt, off_xt, off_ds, off_dst, total;
+      off_c_c, off_adv, off_seq_loss, off_gterm, off_part, off_wt, off_xt, off_ds, off_dst,
+      off_desc, off_ref, off_zsum, off_scale, total;
 };
 
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -466,6 +579,16 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   p.tiles_v = p.Vp / kBM;
   p.n_chunks = (int)((b->R + tc - 1) / tc);
   p.bwd = bwd;
+  // Single-pass backward: bf16 hot-kernel shapes only, and only when the caller bounds the sequence length by a chunk.
+  const int mode = prm ? prm->backward_mode : RL_BWD_AUTO;
+  if (mode != RL_BWD_AUTO && mode != RL_BWD_RECOMPUTE && mode != RL_BWD_STASH) return RL_ERR_RANGE;
+  if (prm && prm->max_seq_len < 0) return RL_ERR_RANGE;
+  const bool can_stash = bwd && b->dtype == RL_BF16 && (b->H % 128 == 0) && prm && prm->max_seq_len > 0 && prm->max_seq_len <= tc &&
+                         ((reinterpret_cast<uintptr_t>(b->hidden) | reinterpret_cast<uintptr_t>(b->weight)) % 16 == 0);
+  if (mode == RL_BWD_STASH && !can_stash) return RL_ERR_RANGE;
+  p.stash = can_stash && mode != RL_BWD_RECOMPUTE;
+  p.max_len = p.stash ? prm->max_seq_len : 0;
+  p.n_desc = 2 * p.n_chunks + 1;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
   const size_t Rp = (size_t)rp + 256;
@@ -483,12 +606,17 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
     p.off_ds = take(p.esz * (size_t)tc * (size_t)p.Vp);
     p.off_dst = take(p.esz * (size_t)p.Vp * (size_t)tc);
   }
+  p.off_desc = p.off_ref = p.off_zsum = p.off_scale = 0;
+  if (p.stash) {
+    p.off_desc = take(sizeof(ChunkDesc) * (size_t)p.n_desc);
+    p.off_ref = take(4 * Rp); p.off_zsum = take(4 * Rp); p.off_scale = take(4 * (size_t)tc);
+  }
   p.total = o;
   return RL_OK;
 }
 
 // The bf16 hot kernel needs an even number of whole 64-element slabs and 16-byte aligned rows; anything else (f32
-// inputs, ragged K) takes the generic kernel.  pfd = L2 prefetch distance of the hot kernel.
+// inputs, ragged K) takes the generic kernel.
 template <class T, class Epi>
 static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi& epi, int tiles, hipStream_t s) {
   static bool attr_set = false;
@@ -500,18 +628,17 @@ static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi&
   kern<<<tiles, kGemmThreads, kGemmSmem, s>>>(A, B, d, epi);
 }
 
-template <class Epi>
-static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, const Epi& epi, int pfd, hipStream_t s) {
+template <class Tune, class Epi>
+static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
   const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
   const bool fast = (d.K % 128 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
                     ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
   if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
-  if (pfd > 0) gemm_nt_bf16_kernel<Epi, 4, 5, 3><<<tiles, 256, 0, s>>>(A, B, d, epi);
-  else gemm_nt_bf16_kernel<Epi, 0, 4, 1><<<tiles, 256, 0, s>>>(A, B, d, epi);
+  gemm_nt_bf16_kernel<Epi, Tune::kPfd, Tune::kVmg, Tune::kVmo><<<tiles, 256, 0, s>>>(A, B, d, epi);
 }
 
-template <class Epi>
-static void launch_gemm(const float* A, const float* B, const GemmDims& d, const Epi& epi, int, hipStream_t s) {
+template <class Tune, class Epi>
+static void launch_gemm(const float* A, const float* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
   const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
   launch_generic<float, Epi>(A, B, d, epi, tiles, s);
 }
@@ -520,6 +647,7 @@ struct Ptrs {
   Ctrl* ctrl; int32_t *seq_len, *cstart, *row_map, *ids_c, *cpos;
   float *zy, *lse_c, *logp_c, *c_c, *adv, *seq_loss, *gterm; float4* part;
   void *wt, *xt, *ds, *dst;
+  ChunkDesc* desc; float *ref, *zsum, *scale;
 };
 
 static Ptrs carve(void* ws, const Plan& p) {
@@ -531,6 +659,8 @@ static Ptrs carve(void* ws, const Plan& p) {
   q.c_c = (float*)(w + p.off_c_c); q.adv = (float*)(w + p.off_adv); q.seq_loss = (float*)(w + p.off_seq_loss);
   q.gterm = (float*)(w + p.off_gterm); q.part = (float4*)(w + p.off_part);
   q.wt = w + p.off_wt; q.xt = w + p.off_xt; q.ds = w + p.off_ds; q.dst = w + p.off_dst;
+  q.desc = (ChunkDesc*)(w + p.off_desc); q.ref = (float*)(w + p.off_ref); q.zsum = (float*)(w + p.off_zsum);
+  q.scale = (float*)(w + p.off_scale);
   return q;
 }
 
@@ -555,9 +685,9 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     const int c0 = ch * p.Tc;
     GemmDims d{};
     d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
-    d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = kBandLogits;
+    d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
     EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V};
-    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm(W, X, d, e, kPrefetchLogits, s); }
+    { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm<TuneLogits>(W, X, d, e, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
     lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
                                                         q.lse_c, q.logp_c, lse_out, logp_out, ent_out);
@@ -581,40 +711,118 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
   {
     ProfScope ps(RL_PROF_TRANSPOSE, s);
     dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
-    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, WT, p.Vp, p.Vp);
+    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp);
   }
   for (int ch = 0; ch < p.n_chunks; ++ch) {
     const int c0 = ch * p.Tc;
     {  // X^T chunk [H][Tc], gathered through row_map, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
-      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, XT, p.Tc, p.Tc);
+      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, nullptr, nullptr, XT, p.Tc, p.Tc);
     }
     {  // recompute logits, form dS and dS^T
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
-      d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = kBandLogits;
+      d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
       EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V};
       ProfScope ps(RL_PROF_GEMM_DS, s);
-      launch_gemm(W, X, d, e, kPrefetchLogits, s);
+      launch_gemm<TuneLogits>(W, X, d, e, s);
     }
     {  // dX = dS W  : A = dS [Tc][Vp], B = W^T [H][Vp]
       GemmDims d{};
       d.M = p.Tc; d.N = p.H; d.K = p.Vp; d.lda = p.Vp; d.ldb = p.Vp;
-      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = kBandDX;
-      EpiDX<T> e{q.row_map, dX, p.H, p.H};
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = TuneDX::kBand;
+      EpiDX<T> e{q.row_map, dX, p.H, p.H, nullptr};
       ProfScope ps(RL_PROF_GEMM_DX, s);
-      launch_gemm(dS, WT, d, e, kPrefetchDX, s);
+      launch_gemm<TuneDX>(dS, WT, d, e, s);
     }
     {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
       GemmDims d{};
       d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
-      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = kBandDW;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = TuneDW::kBand;
+      d.zero_if_empty = (ch == 0);
       EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
       ProfScope ps(RL_PROF_GEMM_DW, s);
-      launch_gemm(dST, XT, d, e, kPrefetchDW, s);
+      launch_gemm<TuneDW>(dST, XT, d, e, s);
     }
   }
+}
+
+// Single-pass variant of forward + loss + backward (bf16 hot kernels): chunks are made of whole
+// sequences, so each chunk's loss coefficients are known as soon as its forward is; the forward
+// keeps the chunk's unnormalised probabilities E (and E^T) and the backward contractions run on
+// them directly: dX = diag(-c/Z) E' W and dW += E'^T diag(-c/Z) X, E' = E with the target entry
+// patched.  Three contractions per chunk instead of four; T x V is still never held, only Tc x V.
+static void run_fused(const rl_batch* b, const rl_params* prm, int objective, const Plan& p, const Ptrs& q,
+                      const rl_outputs* out, hipStream_t s) {
+  typedef bf16_t T;
+  const T* X = static_cast<const T*>(b->hidden);
+  const T* W = static_cast<const T*>(b->weight);
+  T* WT = static_cast<T*>(q.wt); T* XT = static_cast<T*>(q.xt);
+  T* E = static_cast<T*>(q.ds); T* ET = static_cast<T*>(q.dst);
+  T* dX = static_cast<T*>(out->d_hidden);
+  {
+    ProfScope ps(RL_PROF_TRANSPOSE, s);
+    const int rows_per_block = 4;
+    zero_masked_rows_kernel<T><<<(unsigned)((p.R + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(q.cpos, dX, p.R, p.H);
+    dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
+    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp);
+  }
+  {
+    ProfScope ps(RL_PROF_PREP, s);
+    chunk_build_kernel<<<1, 64, 0, s>>>(q.seq_len, q.cstart, p.B, p.Tc, p.max_len, q.desc, p.n_desc, q.ctrl, out->stats);
+    target_logit_kernel<<<(unsigned)((p.R + 3) / 4), 256, 0, s>>>(X, W, p.H, q.row_map, q.ids_c, b->old_logprob, q.ctrl, q.zy, q.ref);
+  }
+  float2* part = reinterpret_cast<float2*>(q.part);
+  for (int k = 0; k < p.n_desc; ++k) {
+    const ChunkDesc* dk = q.desc + k;
+    const int* chunk = &dk->row_start;
+    {  // forward: partial sums + E, E^T
+      GemmDims d{};
+      d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
+      d.b_rows = q.row_map; d.chunk = chunk; d.dyn = 2; d.group_m = TuneLogits::kBand;
+      EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, ET, p.Tc, p.V};
+      ProfScope ps(RL_PROF_GEMM_FWD, s);
+      gemm_nt_bf16_kernel<EpiFwdStash<T>, TuneLogits::kPfd, TuneLogits::kVmg, TuneLogits::kVmo>
+          <<<((p.V + kBM - 1) / kBM) * ((p.Tc + kBN - 1) / kBN), 256, 0, s>>>(W, X, d, e);
+    }
+    {
+      ProfScope ps(RL_PROF_COMBINE, s);
+      lse_sum_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(part, p.Tc, p.tiles_v, q.zy, q.ref, q.row_map, dk, q.lse_c, q.logp_c, q.zsum,
+                                                      out->lse, out->logprob, out->entropy);
+    }
+    {
+      ProfScope ps(RL_PROF_LOSS, s);
+      seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
+                                         b->group_idx, b->log_z, p.B, prm->clip_eps, prm->kl_coef, prm->beta,
+                                         q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats, dk);
+      stash_patch_kernel<T><<<(p.Tc + 255) / 256, 256, 0, s>>>(dk, q.ids_c, q.zy, q.ref, q.zsum, q.c_c, q.scale, E, p.Vp, ET, p.Tc);
+    }
+    {  // X^T chunk scaled by -c/Z, zero beyond the valid rows
+      ProfScope ps(RL_PROF_TRANSPOSE, s);
+      dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
+      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc);
+    }
+    {  // dX = diag(-c/Z) E' W : A = E' [Tc][Vp], B = W^T [H][Vp]
+      GemmDims d{};
+      d.M = p.Tc; d.N = p.H; d.K = p.Vp; d.lda = p.Vp; d.ldb = p.Vp;
+      d.chunk = chunk; d.dyn = 1; d.group_m = TuneDX::kBand;
+      EpiDX<T> e{q.row_map, dX, p.H, p.H, q.scale};
+      ProfScope ps(RL_PROF_GEMM_DX, s);
+      launch_gemm<TuneDX>(E, WT, d, e, s);
+    }
+    {  // dW (+)= E'^T (diag(-c/Z) X) : A = E'^T [Vp][Tc], B = scaled X^T [H][Tc]
+      GemmDims d{};
+      d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
+      d.chunk = chunk; d.dyn = 3; d.zero_if_empty = (k == 0); d.group_m = TuneDW::kBand;
+      EpiDW e{out->d_weight, p.H, p.V, p.H, k > 0 ? 1 : 0};
+      ProfScope ps(RL_PROF_GEMM_DW, s);
+      launch_gemm<TuneDW>(ET, XT, d, e, s);
+    }
+  }
+  ProfScope ps(RL_PROF_LOSS, s);
+  finalize_kernel<<<1, 1024, 0, s>>>(q.seq_loss, q.gterm, b->group_idx, q.seq_len, p.B, p.P, objective, q.ctrl,
+                                    out->loss, out->d_log_z, out->seq_loss);
 }
 
 static rl_status check_ws(void* ws, size_t bytes, const Plan& p) {
@@ -657,7 +865,7 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 101; }
+int32_t rl_version(void) { return 102; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
 
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
@@ -749,6 +957,10 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   if (out->advantages) (void)hipMemcpyAsync(out->advantages, q.adv, 4 * (size_t)p.B, hipMemcpyDeviceToDevice, s);
   }
 
+  if (p.stash) {
+    run_fused(b, prm, objective, p, q, out, s);
+    return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+  }
   if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, out->logprob, out->lse, out->entropy, s);
   else run_forward<float>(b, p, q, out->logprob, out->lse, out->entropy, s);
 
@@ -756,8 +968,8 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   ProfScope ps(RL_PROF_LOSS, s);
   seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
                                      b->group_idx, b->log_z, p.B, prm->clip_eps, prm->kl_coef, prm->beta,
-                                     q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats);
-  finalize_kernel<<<1, 1024, 0, s>>>(q.seq_loss, q.gterm, b->group_idx, q.seq_len, p.B, p.P, objective,
+                                     q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats, nullptr);
+  finalize_kernel<<<1, 1024, 0, s>>>(q.seq_loss, q.gterm, b->group_idx, q.seq_len, p.B, p.P, objective, q.ctrl,
                                     out->loss, out->d_log_z, out->seq_loss);
   }
   if (bwd) {

@@ -39,9 +39,15 @@ def run_oracle(b, objective: str, want_dw=True, **over):
                                    **inp, **kw)
 
 
-def run_gpu(b, objective: str, chunk_rows=0, backward=True, **over):
+def run_gpu(b, objective: str, chunk_rows=0, backward=True, mode=None, **over):
+    """mode: None (library default without a length promise = recompute), "recompute", or "stash" (the
+    single-pass backward, with max_seq_len promised as the batch's longest sequence)."""
     c = b.cfg
     kw = dict(clip_eps=c.clip_eps, kl_coef=c.kl_coef, beta=c.beta, adv_eps=c.adv_eps, adv_std_ddof=c.adv_std_ddof)
+    if mode == "stash":
+        kw.update(backward_mode="stash", max_seq_len=max(int(b.lengths.max()), 1))
+    elif mode == "recompute":
+        kw.update(backward_mode="recompute")
     kw.update(over)
     res = binding.rl_policy_loss_fwd_bwd(OBJ[objective][1], b.hidden, b.weight, b.token_ids, b.mask, b.cu_seqlens,
                                          b.group_idx, b.rewards, b.old_logprob, b.ref_logprob, b.log_z, P=c.P,

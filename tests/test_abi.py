@@ -68,6 +68,25 @@ def test_workspace_query_and_shape_errors(lib):
     assert lib.rl_workspace_bytes(C.byref(_batch(dtype=binding.RL_F32, H=60)), None, 1, C.byref(n)) == 0
 
 
+def test_backward_mode_is_validated_on_the_host(lib):
+    n, m = C.c_size_t(0), C.c_size_t(0)
+    ok = _batch(R=100000, H=128)
+    mk = binding.make_params
+    # the single-pass backward needs bf16, H % 128 == 0 and a length promise that fits a chunk
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="stash", max_seq_len=512)), 1, C.byref(n)) == 0
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="recompute", max_seq_len=512)), 1, C.byref(m)) == 0
+    assert n.value > m.value                                                     # chunk records, references, factors
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="auto", max_seq_len=512)), 1, C.byref(m)) == 0
+    assert m.value == n.value                                                    # auto picks it when it can
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="stash")), 1, C.byref(n)) == 4            # no promise
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="stash", max_seq_len=512, chunk_rows=256)), 1, C.byref(n)) == 4
+    assert lib.rl_workspace_bytes(C.byref(_batch(H=64)), C.byref(mk(backward_mode="stash", max_seq_len=8)), 1, C.byref(n)) == 4
+    assert lib.rl_workspace_bytes(C.byref(_batch(H=128, dtype=binding.RL_F32)), C.byref(mk(backward_mode="stash", max_seq_len=8)), 1, C.byref(n)) == 4
+    assert lib.rl_workspace_bytes(C.byref(_batch(H=64)), C.byref(mk(backward_mode="auto", max_seq_len=8)), 1, C.byref(n)) == 0   # falls back
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode=7)), 1, C.byref(n)) == 4
+    assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(max_seq_len=-1)), 1, C.byref(n)) == 4
+
+
 def test_null_and_range_errors_are_rejected_on_the_host(lib):
     b = _batch()
     prm = binding.make_params()

@@ -64,9 +64,10 @@ def test_bf16_sub_sampled(name):
     _say(name, "sub-sampled: R", b.R, "T", b.T, "H", b.cfg.H, "V", b.cfg.V)
     for objective in ("grpo", "flow"):
         ref = run_oracle(b, objective)
-        res = run_gpu(b, objective, chunk_rows=1024 if name == "small" else 0)
-        err = compare_all(b, res, ref, **BF16_TOL)
-        _say("  ", objective, err)
+        for mode in ("recompute", "stash"):          # both backward modes against the same oracle result
+            res = run_gpu(b, objective, chunk_rows=1024 if name == "small" else 0, mode=mode)
+            err = compare_all(b, res, ref, **BF16_TOL)
+            _say("  ", objective, mode, err)
         # properties that hold at any size
         dW = f64(res.d_weight)
         assert np.abs(dW.sum(0)).max() <= 1e-3 * np.abs(dW).max() * np.sqrt(dW.shape[0])
@@ -131,6 +132,39 @@ def test_zero_variance_groups_and_ddof():
             assert torch.all(res.advantages[:4] == 0)
 
 
+@pytest.mark.parametrize("layout", ["padded", "packed"])
+def test_stash_mode_edges(layout):
+    # single-pass backward: sequence-aligned chunks of 256 rows (empty, single-token and chunk-filling sequences,
+    # several sequences per chunk, a chunk boundary after every kind), ragged vocabulary, targets on tile borders
+    V, H = 1000, 128
+    lengths = [0, 1, 5, 37, 0, 200, 256, 56, 3, 1, 64, 2, 190, 66, 0, 255]
+    ids = [0, 255, 256, 511, 512, V - 1, 127, 128, 999, 1, 254, 257]
+    b = _edge_batch("bf16", H, V, lengths, P=4, G=4, ids=ids, layout=layout)
+    for objective in ("grpo", "flow"):
+        ref = run_oracle(b, objective)
+        res = run_gpu(b, objective, chunk_rows=256, mode="stash")
+        compare_all(b, res, ref, **BF16_TOL)
+        res2 = run_gpu(b, objective, chunk_rows=256, mode="stash")
+        assert torch.equal(res.d_weight, res2.d_weight) and torch.equal(res.d_hidden, res2.d_hidden) and torch.equal(res.loss, res2.loss)
+
+
+def test_stash_mode_no_tokens_and_broken_promise():
+    b = _edge_batch("bf16", 128, 512, [0, 0, 0, 0], P=2, G=2)
+    res = run_gpu(b, "flow", mode="stash")
+    assert float(res.loss.item()) == 0.0
+    assert torch.count_nonzero(res.d_weight) == 0 and torch.count_nonzero(res.d_hidden) == 0
+    # a sequence longer than promised: counted, and the loss comes back NaN instead of a silently wrong number
+    b = _edge_batch("bf16", 128, 512, [6, 40, 7, 3], P=2, G=2)
+    res = run_gpu(b, "grpo", mode="stash", max_seq_len=8)
+    assert res.stats_dict()["n_seq_too_long"] == 1
+    assert np.isnan(float(res.loss.item()))
+    # the same batch with an honest promise is fine again (the flag does not stick)
+    ref = run_oracle(b, "grpo")
+    res = run_gpu(b, "grpo", mode="stash")
+    compare_all(b, res, ref, **BF16_TOL)
+    assert res.stats_dict()["n_seq_too_long"] == 0
+
+
 def test_out_of_range_token_ids_are_masked_and_counted():
     b = _edge_batch("bf16", 64, 512, [6, 4, 7, 3], P=2, G=2, layout="packed")
     bad_rows = [1, 9, 19]
@@ -172,7 +206,8 @@ def test_results_are_bit_reproducible():
 
 # --------------------------------------------------------------------------- full size, bench launch configuration
 @pytest.mark.timeout(900)
-def test_7b_full_size_sampled_sequences():
+@pytest.mark.parametrize("mode", ["recompute", "stash"])
+def test_7b_full_size_sampled_sequences(mode):
     """The 7B-shaped configuration at full size, padded layout, default chunking (what bench.py
     times).  The oracle cannot do 1.6e14 MACs per pass, so it computes, one by one, everything that
     belongs to the two shortest sequences (log-probs, lse, sequence loss, per-token coefficient, dX
@@ -199,7 +234,7 @@ def test_7b_full_size_sampled_sequences():
     gidx = np_bits(b.group_idx).astype(np.int64)
     X64 = None
     for objective in ("grpo", "flow"):
-        res = run_gpu(b, objective)
+        res = run_gpu(b, objective, mode=mode)
         # exact integer work at full size
         np.testing.assert_array_equal(res.seq_len.cpu().numpy(), lengths)
         st = res.stats_dict()
