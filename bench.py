@@ -129,13 +129,14 @@ def main():
     thv = float(T) * cfg.H * cfg.V
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     # dominant kernel: the contraction class with the largest share of the step
-    gemms = {k: prof[k] for k in ("gemm_fwd", "gemm_ds", "gemm_dx", "gemm_dw")}
+    # flops of one step per launch class: each contraction is 2*T*H*V; gemm_bwd is dX and dW in one launch
+    class_flops = {"gemm_fwd": 2.0 * thv, "gemm_ds": 2.0 * thv, "gemm_dx": 2.0 * thv, "gemm_dw": 2.0 * thv, "gemm_bwd": 4.0 * thv}
+    gemms = {k: prof[k] for k in class_flops}
     dom = max(gemms, key=lambda k: gemms[k][0])
     dom_ms, dom_n = gemms[dom]
-    flops_per_step_class = 2.0 * thv                       # each of the four contractions: 2*T*H*V
-    achieved = flops_per_step_class * a.steps / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    achieved = class_flops[dom] * a.steps / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     kernels = {k: {"ms_per_step": v[0] / a.steps, "launches_per_step": v[1] / a.steps,
-                   "tflops": (2.0 * thv * a.steps / (v[0] * 1e-3) / 1e12) if (k in gemms and v[0] > 0) else None}
+                   "tflops": (class_flops[k] * a.steps / (v[0] * 1e-3) / 1e12) if (k in gemms and v[0] > 0) else None}
                for k, v in prof.items()}
     out = {
         "metric": "rollout tokens/sec, fused logprob+policy-loss fwd+bwd; % bf16 MFMA peak",
@@ -151,7 +152,7 @@ def main():
         "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
         "roofline": {"bound": "mfma", "kernel": f"gemm_nt_bf16_kernel ({dom})", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": (MEASURED_TRAFFIC_7B_CHUNK32768[dom]
+                     "traffic": (MEASURED_TRAFFIC_7B_CHUNK32768.get(dom)
                                  if (a.config == "7b" and a.len_div == 1 and a.layout == "padded"
                                      and (a.chunk_rows or 32768) == 32768) else None),
                      "traffic_note": "bytes per full 32768-row launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",

@@ -166,7 +166,8 @@ enum { RL_PROF_PREP = 0,       /* counts, scan, compaction, output zero-fill    
        RL_PROF_GEMM_DS = 5,    /* recomputed logits -> dS, dS^T                         */
        RL_PROF_GEMM_DX = 6,    /* dX = dS W                                             */
        RL_PROF_GEMM_DW = 7,    /* dW += dS^T X                                          */
-       RL_PROF_CLASSES = 8 };
+       RL_PROF_GEMM_BWD = 8,   /* single-pass backward: dX and dW of a chunk in one launch */
+       RL_PROF_CLASSES = 9 };
 typedef struct rl_profile {     /* host struct */
   double  ms[RL_PROF_CLASSES];
   int64_t launches[RL_PROF_CLASSES];

@@ -47,11 +47,11 @@ class rl_outputs(C.Structure):
                 ("entropy", C.c_void_p)]
 
 
-PROF_CLASSES = ("prep", "gemm_fwd", "combine", "loss", "transpose", "gemm_ds", "gemm_dx", "gemm_dw")
+PROF_CLASSES = ("prep", "gemm_fwd", "combine", "loss", "transpose", "gemm_ds", "gemm_dx", "gemm_dw", "gemm_bwd")
 
 
 class rl_profile(C.Structure):
-    _fields_ = [("ms", C.c_double * 8), ("launches", C.c_int64 * 8)]
+    _fields_ = [("ms", C.c_double * 9), ("launches", C.c_int64 * 9)]
 
 
 STATS_FIELDS = ("n_tokens", "n_clip_hi", "n_clip_lo", "n_bad_token", "n_bad_group", "n_bad_seq", "n_seq_too_long")

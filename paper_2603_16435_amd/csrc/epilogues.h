@@ -27,6 +27,8 @@ template <> __device__ inline float exp_shifted<float>(float z, float m, float) 
 //      u feeds the entropy H_t = lse_t - u/s of the full distribution at no extra pass.
 template <class T>
 struct EpiFwd {
+  typedef NoPre Pre;
+  template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = false;
   __device__ void keep_alive() const { zy_c[0] = 0.f; }
   const int* ids_c;     // [chunk-global compact row] sampled token
@@ -67,7 +69,7 @@ struct EpiFwd {
   }
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d, const Pre& pre) const {
     float4* red = reinterpret_cast<float4*>(smem);              // [WAVES_M][BN]
     const float NEG = -__builtin_inff();
     const int vleft = V - c.m0;                                 // rows of this sub-tile below vleft are real vocabulary
@@ -137,6 +139,17 @@ struct EpiFwd {
 //      directly, with the target entry patched and the factor applied per token.
 template <class T>
 struct EpiFwdStash {
+  struct Pre { float rl[8]; };                            // ref_t * log2(e) of the lane's eight token columns
+  template <class L> __device__ Pre preload(const TileCtx& c, const GemmDims& d) const {
+    Pre p;
+    const int cc = c.lane & 15;
+#pragma unroll
+    for (int bj = 0; bj < 8; ++bj) {
+      const int n = c.n0 + perm_col(bj, cc);
+      p.rl[bj] = (n < c.Nv) ? ref_l2e[d.chunk_start + n] : __builtin_inff();   // column without a token: e = exp2(-inf) = 0
+    }
+    return p;
+  }
   static constexpr bool kPermute = true;
   __device__ void keep_alive() const { E[0] = (T)0.f; }
   const float* ref_l2e;   // [compact row] ref_t * log2(e)
@@ -184,17 +197,13 @@ struct EpiFwdStash {
   }
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d, const Pre& pre) const {
     static_assert(L::kBlk == 16 && MB == 8 && NB == 8 && sizeof(T) == 2, "hot kernel only");
     float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
     const int g = c.lane >> 4, cc = c.lane & 15;
     float rl[NB], sm[NB], su[NB];
 #pragma unroll
-    for (int bj = 0; bj < NB; ++bj) {
-      const int n = c.n0 + perm_col(bj, cc);
-      rl[bj] = (n < c.Nv) ? ref_l2e[d.chunk_start + n] : __builtin_inff();   // column without a token: e = exp2(-inf) = 0
-      sm[bj] = 0.f; su[bj] = 0.f;
-    }
+    for (int bj = 0; bj < NB; ++bj) { rl[bj] = pre.rl[bj]; sm[bj] = 0.f; su[bj] = 0.f; }
     const int vleft = V - c.m0;                            // sub-tile rows >= vleft are vocabulary padding
     if (vleft < MB * L::kBlk) body<L, MB, NB, AGPR, true>(acc, c, g, cc, vleft, rl, sm, su);   // wavefront-uniform
     else body<L, MB, NB, AGPR, false>(acc, c, g, cc, vleft, rl, sm, su);
@@ -241,6 +250,8 @@ template <> struct Pack4<float> {
 //      copies then leave in 16-byte stores, 64 per wavefront and tile, with no staging through LDS.
 template <class T>
 struct EpiDS {
+  typedef NoPre Pre;
+  template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = true;
   __device__ void keep_alive() const { dS[0] = (T)0.f; }
   const int* ids_c; const float* lse_c; const float* c_c;
@@ -249,7 +260,7 @@ struct EpiDS {
   int V;
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d, const Pre&) const {
     if constexpr (L::kBlk == 16 && sizeof(T) == 2) {
       static_assert(MB == 8 && NB == 8, "the relabelling is written for 128x128 wavefront sub-tiles");
       const int g = c.lane >> 4, cc = c.lane & 15;
@@ -328,6 +339,8 @@ struct EpiDS {
 // ---- backward, stage 2: dX tile -> rows scattered back to their original positions
 template <class T>
 struct EpiDX {
+  typedef NoPre Pre;
+  template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = false;
   __device__ void keep_alive() const { dX[0] = (T)0.f; }
   const int* row_map;   // compact row -> original row
@@ -335,7 +348,7 @@ struct EpiDX {
   const float* row_scale;   // optional [chunk row]: factor applied to the whole row
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d) const {
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d, const Pre&) const {
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
@@ -353,27 +366,44 @@ struct EpiDX {
   }
 };
 
-// ---- backward, stage 3: dW tile, f32, overwritten by the first chunk and accumulated after
+// ---- backward, stage 3: dW tile, f32, overwritten by the first chunk and accumulated after.
+//      When accumulating, the old values of a whole block row are fetched first (32 loads in flight)
+//      and only then added and stored: a load-add-store per element would pay the memory latency
+//      256 times per tile.
 struct EpiDW {
+  typedef NoPre Pre;
+  template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = false;
   __device__ void keep_alive() const { dW[0] = 0.f; }
   float* dW; int64_t ldw; int V, H; int accumulate;
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
-  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&) const {
+  __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims&, const Pre&) const {
+    constexpr int RUN = L::kRegs < 4 ? L::kRegs : 4;      // registers handled per round: 4 rows x NB columns
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
-      for (int i = 0; i < L::kRegs; ++i) {
-        const int m = c.m0 + L::row(bi, i, c.lane);
-        if (m >= V) continue;
+      for (int q = 0; q < L::kRegs / RUN; ++q) {
+        float old[RUN][NB];
+        if (accumulate) {
 #pragma unroll
-        for (int bj = 0; bj < NB; ++bj) {
-          const int n = c.n0 + L::col(bj, c.lane);
-          if (n < H) {
-            float* p = dW + (int64_t)m * ldw + n;
-            const float v = acc_read<AGPR>(acc[bi][bj], i);
-            *p = accumulate ? (*p + v) : v;
+          for (int e = 0; e < RUN; ++e) {
+            const int m = c.m0 + L::row(bi, q * RUN + e, c.lane);
+#pragma unroll
+            for (int bj = 0; bj < NB; ++bj) {
+              const int n = c.n0 + L::col(bj, c.lane);
+              old[e][bj] = (m < V && n < H) ? dW[(int64_t)m * ldw + n] : 0.f;
+            }
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < RUN; ++e) {
+          const int m = c.m0 + L::row(bi, q * RUN + e, c.lane);
+#pragma unroll
+          for (int bj = 0; bj < NB; ++bj) {
+            const int n = c.n0 + L::col(bj, c.lane);
+            const float v = acc_read<AGPR>(acc[bi][bj], q * RUN + e);
+            if (m < V && n < H) dW[(int64_t)m * ldw + n] = accumulate ? old[e][bj] + v : v;
           }
         }
       }

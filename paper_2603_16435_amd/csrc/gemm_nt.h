@@ -128,6 +128,7 @@ struct TileCtx {
   int tid;
 };
 template <int> struct Int {};
+struct NoPre {};      // epilogue with nothing to fetch ahead of the main loop
 
 // Accumulator layouts: where register i of block (bi, bj) of a lane sits inside the wavefront's
 // sub-tile.  Registers come in runs of four consecutive rows of one column.
@@ -259,7 +260,8 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
   TileCtx c;
   c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
   c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
-  epi.template run<Layout32, MB, NB, BM, BN, WAVES_M, WAVES_N, false>(acc, c, smem, d);
+  const typename Epi::Pre pre = epi.template preload<Layout32>(c, d);
+  epi.template run<Layout32, MB, NB, BM, BN, WAVES_M, WAVES_N, false>(acc, c, smem, d, pre);
 }
 
 // ------------------------------------------------------------------ bf16 hot kernel
@@ -292,25 +294,29 @@ __device__ __attribute__((always_inline)) inline void mfma_drain() { asm volatil
 
 // PFD: L2 prefetch distance in slabs (0 = none).  VMG / VMO: inside a phase of 32 MFMAs the slab loads
 // are issued after MFMA number VMO, VMO + VMG, VMO + 2 VMG, ...
+constexpr int kHotStageBytes = (256 + 256) * kSlabBytes;      // one LDS stage of the hot kernel: a slab of A and of B
+
+// The work of one workgroup of the hot kernel: tile number `pid` of the contraction (A, B, d) into epi.
+// stage0 / stage1 are the caller's two LDS stages; they must be separate objects so that the compiler
+// can tell the stage being filled by the DMA loads from the stage the fragments are read from and
+// does not serialise them with a vmcnt(0).
 template <class Epi, int PFD, int VMG, int VMO>
-__global__ __launch_bounds__(256)
-void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, Epi epi) {
+__device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d,
+                                                                        const Epi& epi, int pid, unsigned char* stage0, unsigned char* stage1) {
   constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2;
   constexpr int WM = 128, WN = 128, MB = 8, NB = 8;             // 8 x 8 blocks of 16 x 16 per wavefront
   constexpr int DSG = 2;                                        // one fragment read per DSG MFMAs
   constexpr int A_BYTES = BM * kSlabBytes, B_BYTES = BN * kSlabBytes, STAGE = A_BYTES + B_BYTES;
   static_assert(VMO < VMG && 5 * VMG + VMO < 32, "six slab loads must fit into a phase");
-  // two separate objects: the compiler can then tell the stage being filled by the DMA loads from the
-  // stage the fragments are read from, and does not serialise them with a vmcnt(0)
-  __shared__ __attribute__((aligned(1024))) unsigned char stage0[STAGE];
-  __shared__ __attribute__((aligned(1024))) unsigned char stage1[STAGE];
+  static_assert(STAGE == kHotStageBytes, "stage size");
 
   int M, N, K;
   if (!resolve_dims(d, M, N, K)) return;
   const int nk = K / BK;
   const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   int tm, tn;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, d.group_m, tm, tn);
+  if (pid >= tiles_m * tiles_n) return;
+  tile_of_block(pid, tiles_m, tiles_n, d.group_m, tm, tn);
   if (tm * BM >= M || tn * BN >= N) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -367,6 +373,12 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
       slot = *reinterpret_cast<const unsigned*>(pf_ptr + (int64_t)k * pf_stride);
     }
   };
+
+  TileCtx c;
+  c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
+  c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
+  // what the epilogue needs from memory per column or row (a few registers): fetched now, used after the main loop
+  const typename Epi::Pre pre = epi.template preload<Layout16>(c, d);
 
   floatx4 acc[MB][NB];
 #pragma unroll
@@ -444,11 +456,29 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
   __syncthreads();
   mfma_drain();
 
-  TileCtx c;
-  c.m0 = tm * BM + wm * WM; c.n0 = tn * BN + wn * WN;
-  c.Mv = M; c.Nv = N; c.lane = lane; c.wm = wm; c.wn = wn; c.tile_m = tm; c.tile_n = tn; c.tid = tid;
-  epi.template run<Layout16, MB, NB, BM, BN, WAVES_M, WAVES_N, true>(acc, c, stage0, d);
+  epi.template run<Layout16, MB, NB, BM, BN, WAVES_M, WAVES_N, true>(acc, c, stage0, d, pre);
   if (PFD > 0 && (pf_sink ^ pf0 ^ pf1) == 0x9E3779B9u && K < 0) epi.keep_alive();   // never true: keeps the prefetch loads
+}
+
+template <class Epi, int PFD, int VMG, int VMO>
+__global__ __launch_bounds__(256)
+void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, Epi epi) {
+  __shared__ __attribute__((aligned(1024))) unsigned char stage0[kHotStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char stage1[kHotStageBytes];
+  gemm_nt_bf16_tile<Epi, PFD, VMG, VMO>(A, B, d, epi, blockIdx.x, stage0, stage1);
+}
+
+// Two independent contractions in one launch: workgroups [0, n1) work on the first, the rest on the
+// second.  Used where one of them alone has too few tiles to fill the last round of the 256 CUs: the
+// other's workgroups then fill the tail.  n1 must be a multiple of the XCD count (tile order).
+template <class Epi1, int PFD1, int VMG1, int VMO1, class Epi2, int PFD2, int VMG2, int VMO2>
+__global__ __launch_bounds__(256)
+void gemm_nt_bf16_pair_kernel(const bf16_t* __restrict__ A1, const bf16_t* __restrict__ B1, GemmDims d1, Epi1 epi1, int n1,
+                              const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2, GemmDims d2, Epi2 epi2) {
+  __shared__ __attribute__((aligned(1024))) unsigned char stage0[kHotStageBytes];
+  __shared__ __attribute__((aligned(1024))) unsigned char stage1[kHotStageBytes];
+  if ((int)blockIdx.x < n1) gemm_nt_bf16_tile<Epi1, PFD1, VMG1, VMO1>(A1, B1, d1, epi1, blockIdx.x, stage0, stage1);
+  else gemm_nt_bf16_tile<Epi2, PFD2, VMG2, VMO2>(A2, B2, d2, epi2, (int)blockIdx.x - n1, stage0, stage1);
 }
 
 }  // namespace rlk

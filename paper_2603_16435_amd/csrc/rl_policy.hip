@@ -803,21 +803,22 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
       transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc);
     }
-    {  // dX = diag(-c/Z) E' W : A = E' [Tc][Vp], B = W^T [H][Vp]
-      GemmDims d{};
-      d.M = p.Tc; d.N = p.H; d.K = p.Vp; d.lda = p.Vp; d.ldb = p.Vp;
-      d.chunk = chunk; d.dyn = 1; d.group_m = TuneDX::kBand;
-      EpiDX<T> e{q.row_map, dX, p.H, p.H, q.scale};
-      ProfScope ps(RL_PROF_GEMM_DX, s);
-      launch_gemm<TuneDX>(E, WT, d, e, s);
-    }
-    {  // dW (+)= E'^T (diag(-c/Z) X) : A = E'^T [Vp][Tc], B = scaled X^T [H][Tc]
-      GemmDims d{};
-      d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
-      d.chunk = chunk; d.dyn = 3; d.zero_if_empty = (k == 0); d.group_m = TuneDW::kBand;
-      EpiDW e{out->d_weight, p.H, p.V, p.H, k > 0 ? 1 : 0};
-      ProfScope ps(RL_PROF_GEMM_DW, s);
-      launch_gemm<TuneDW>(ET, XT, d, e, s);
+    {  // dX = diag(-c/Z) E' W  (A = E' [Tc][Vp], B = W^T [H][Vp]) and dW (+)= E'^T (diag(-c/Z) X)  (A = E'^T [Vp][Tc],
+       // B = scaled X^T [H][Tc]) in one launch: dX alone has too few (long) tiles to fill its last round of CUs
+      GemmDims dx{};
+      dx.M = p.Tc; dx.N = p.H; dx.K = p.Vp; dx.lda = p.Vp; dx.ldb = p.Vp;
+      dx.chunk = chunk; dx.dyn = 1; dx.group_m = TuneDX::kBand;
+      EpiDX<T> ex{q.row_map, dX, p.H, p.H, q.scale};
+      GemmDims dw{};
+      dw.M = p.V; dw.N = p.H; dw.K = p.Tc; dw.lda = p.Tc; dw.ldb = p.Tc;
+      dw.chunk = chunk; dw.dyn = 3; dw.zero_if_empty = (k == 0); dw.group_m = TuneDW::kBand;
+      EpiDW ew{out->d_weight, p.H, p.V, p.H, k > 0 ? 1 : 0};
+      const int tn = (p.H + kBN - 1) / kBN;
+      const int n1 = (((p.Tc + kBM - 1) / kBM) * tn + kXcds - 1) / kXcds * kXcds;
+      const int n2 = ((p.V + kBM - 1) / kBM) * tn;
+      ProfScope ps(RL_PROF_GEMM_BWD, s);
+      gemm_nt_bf16_pair_kernel<EpiDX<T>, TuneDX::kPfd, TuneDX::kVmg, TuneDX::kVmo, EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo>
+          <<<n1 + n2, 256, 0, s>>>(E, WT, dx, ex, n1, ET, XT, dw, ew);
     }
   }
   ProfScope ps(RL_PROF_LOSS, s);
