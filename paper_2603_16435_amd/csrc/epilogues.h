@@ -155,8 +155,8 @@ struct EpiFwdStash {
   const float* ref_l2e;   // [compact row] ref_t * log2(e)
   float2* part;           // [tiles_m(V)][ldp] partial (s, u) per token of the chunk
   int ldp;
-  T* E;  int64_t ld_e;    // [chunk rows][Vp]
-  T* ET; int64_t ld_et;   // [Vp][chunk rows]
+  T* E;  int64_t ld_e;    // [chunk rows][Vp = ld_e], slab-tiled
+  T* ET; int64_t ld_et;   // [Vp][chunk rows = ld_et], slab-tiled
   int V;
 
   // exponentials, sums and the two stores for block rows 2k, 2k+1 (k = 0..3), eight token columns each
@@ -183,14 +183,14 @@ struct EpiFwdStash {
         bf16x8 row;
 #pragma unroll
         for (int i = 0; i < 8; ++i) row[i] = (bf16_t)ev[i];
-        *reinterpret_cast<bf16x8*>(E + (int64_t)(c.n0 + perm_col(bj, cc)) * ld_e + c.m0 + mrel) = row;
+        *reinterpret_cast<bf16x8*>(E + tiled_index(c.n0 + perm_col(bj, cc), c.m0 + mrel, ld_e)) = row;
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         bf16x8 col;
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj) col[bj] = et[i][bj >> 1][bj & 1];
-        *reinterpret_cast<bf16x8*>(ET + (int64_t)(c.m0 + mrel + i) * ld_et + c.n0 + cc * 8) = col;
+        *reinterpret_cast<bf16x8*>(ET + tiled_index(c.m0 + mrel + i, c.n0 + cc * 8, ld_et)) = col;
       }
       __builtin_amdgcn_sched_barrier(0);                  // keep the four rounds apart: 64 live values each is plenty
     }
@@ -258,6 +258,7 @@ struct EpiDS {
   T* dS;  int64_t ld_ds;    // [chunk rows][Vp]
   T* dST; int64_t ld_dst;   // [Vp][chunk rows]
   int V;
+  bool tiled;               // both copies slab-tiled (always so for bf16: their consumer is the hot kernel)
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d, const Pre&) const {
@@ -296,14 +297,14 @@ struct EpiDS {
           bf16x8 v;
 #pragma unroll
           for (int i = 0; i < 8; ++i) v[i] = o[bj][i];
-          *reinterpret_cast<bf16x8*>(dS + (int64_t)(c.n0 + perm_col(bj, cc)) * ld_ds + c.m0 + mrel) = v;
+          *reinterpret_cast<bf16x8*>(dS + tiled_index(c.n0 + perm_col(bj, cc), c.m0 + mrel, ld_ds)) = v;
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           bf16x8 v;
 #pragma unroll
           for (int bj = 0; bj < NB; ++bj) v[bj] = o[bj][i];
-          *reinterpret_cast<bf16x8*>(dST + (int64_t)(c.m0 + mrel + i) * ld_dst + c.n0 + cc * 8) = v;
+          *reinterpret_cast<bf16x8*>(dST + tiled_index(c.m0 + mrel + i, c.n0 + cc * 8, ld_dst)) = v;
         }
       }
     } else {
@@ -327,9 +328,9 @@ struct EpiDS {
               const float ds = ct * (((m + e) == y ? 1.f : 0.f) - p);
               o[e] = (valid && (m + e) < V) ? ds : 0.f;
             }
-            Pack4<T>::store(dS + (int64_t)n * ld_ds + m, o[0], o[1], o[2], o[3]);
+            Pack4<T>::store(dS + operand_index(tiled, n, m, ld_ds), o[0], o[1], o[2], o[3]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dST[(int64_t)(m + e) * ld_dst + n] = (T)o[e];
+            for (int e = 0; e < 4; ++e) dST[operand_index(tiled, m + e, n, ld_dst)] = (T)o[e];
           }
       }
     }

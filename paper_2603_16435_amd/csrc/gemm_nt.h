@@ -55,10 +55,21 @@ struct GemmDims {
   int chunk_start;        // first compacted row of this chunk
   const int* chunk;       // if set, device pair {first compacted row, rows} of this chunk; replaces n_real / chunk_start,
                           // and the gather tables are then indexed from the chunk's first row
+  int a_tiled, b_tiled;   // hot kernel only: operand stored slab-tiled (see tiled_index) instead of row-major; K is then its full K extent
   int dyn;                // which extent is min(rows left in the chunk, bound): 0 none, 1 M, 2 N, 3 K (rounded up to 256)
   int zero_if_empty;      // dyn == 3 only: an empty chunk still runs the epilogue (with K = 0) instead of returning
   int group_m;            // tile-order parameter: M-tiles per band
 };
+
+// Slab-tiled operand layout of the library's own bf16 work buffers: [row / 256][k / 64][256 rows][64 k].
+// The 32 KiB that a workgroup loads per operand and slab are then contiguous in memory (one page, one DRAM
+// row run) instead of 256 pieces of 128 bytes a whole matrix row apart; K is the buffer's full K extent.
+__device__ __host__ inline int64_t tiled_index(int r, int k, int64_t K) {
+  return (int64_t)(r >> 8) * (K * 256) + (int64_t)(k >> 6) * 16384 + ((r & 255) << 6) + (k & 63);
+}
+__device__ __host__ inline int64_t operand_index(bool tiled, int r, int k, int64_t ld) {
+  return tiled ? tiled_index(r, k, ld) : (int64_t)r * ld + k;
+}
 
 // Apply the dynamic extent.  Returns false if this launch has nothing to do.
 __device__ inline bool resolve_dims(GemmDims& d, int& M, int& N, int& K) {
@@ -334,16 +345,17 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
     const int c = (lane & 7) ^ ((lr >> 1) & 7);
     int r = tm * BM + (Epi::kPermute ? perm_lds_row_a(lr) : lr); r = r < M ? r : M - 1;
     if (d.a_rows) r = d.a_rows[r];
-    ap[j] = A + (int64_t)r * d.lda + c * 8;
+    ap[j] = A + (d.a_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.lda) + c * 8;
     r = tn * BN + (Epi::kPermute ? perm_lds_row_b(lr) : lr); r = r < N ? r : N - 1;
     if (d.b_rows) r = d.b_rows[r];
-    bp[j] = B + (int64_t)r * d.ldb + c * 8;
+    bp[j] = B + (d.b_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.ldb) + c * 8;
   }
+  const int a_ks = d.a_tiled ? 16384 : BK, b_ks = d.b_tiled ? 16384 : BK;     // elements from one slab to the next
   // load j of the 16 per slab (0..7 = A rows, 8..15 = B rows)
-  auto issue1 = [&](int k0, unsigned char* stage, int j) __attribute__((always_inline)) {
+  auto issue1 = [&](int slab, unsigned char* stage, int j) __attribute__((always_inline)) {
     unsigned char* as = stage + wave * 64 * kSlabBytes;
-    if (j < 8) load16_to_lds(ap[j] + k0, as + j * 8 * kSlabBytes);
-    else load16_to_lds(bp[j - 8] + k0, as + A_BYTES + (j - 8) * 8 * kSlabBytes);
+    if (j < 8) load16_to_lds(ap[j] + (int64_t)slab * a_ks, as + j * 8 * kSlabBytes);
+    else load16_to_lds(bp[j - 8] + (int64_t)slab * b_ks, as + A_BYTES + (j - 8) * 8 * kSlabBytes);
   };
 
   // ---- L2 prefetch.  The workgroups resident on one XCD at a time form (about) a block of 8 M-tiles
@@ -352,15 +364,17 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   // between them the block's workgroups cover every line once.  Wavefronts 2 and 3 execute the same
   // instruction on one fixed line (no divergent control flow around the accumulators).
   const unsigned char* pf_ptr;
-  int pf_stride = BK * 2;
+  int pf_stride;
   if (wave == 0) {
     int r = tm * BM + 64 * (tn & 3) + lane; r = r < M ? r : M - 1;
     if (d.a_rows) r = d.a_rows[r];
-    pf_ptr = reinterpret_cast<const unsigned char*>(A + (int64_t)r * d.lda);
+    pf_ptr = reinterpret_cast<const unsigned char*>(A + (d.a_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.lda));
+    pf_stride = a_ks * 2;
   } else if (wave == 1) {
     int r = tn * BN + 32 * (tm & 7) + (lane & 31); r = r < N ? r : N - 1;
     if (d.b_rows) r = d.b_rows[r];
-    pf_ptr = reinterpret_cast<const unsigned char*>(B + (int64_t)r * d.ldb);
+    pf_ptr = reinterpret_cast<const unsigned char*>(B + (d.b_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.ldb));
+    pf_stride = b_ks * 2;
   } else {
     pf_ptr = reinterpret_cast<const unsigned char*>(A);
     pf_stride = 0;
@@ -396,7 +410,7 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   const int arow = (wm * WM + frow) * kSlabBytes, brow = A_BYTES + (wn * WN + frow) * kSlabBytes;
   const int swz = (frow >> 1) & 7;                 // the other row blocks are 16 rows apart: same swizzle
   u32x4_t fa[2][MB], fb[2][NB / 2];
-  auto kof = [&](int k) __attribute__((always_inline)) { return (k < nk ? k : nk - 1) * BK; };   // past the end: harmless re-load
+  auto kof = [&](int k) __attribute__((always_inline)) { return k < nk ? k : nk - 1; };   // slab number; past the end: harmless re-load
 
   // One phase = 32 MFMAs on (fa[aset], fb[bset]) into column half `half`, with, at fixed places between them,
   //  * fragment reads for the next phase, one per DSG MFMAs.  kind 4: fb[bset^1] <- B blocks 4..7 of

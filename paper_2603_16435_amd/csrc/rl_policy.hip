@@ -324,8 +324,8 @@ __global__ void stash_patch_kernel(const ChunkDesc* desc, const int32_t* ids_c, 
   const float ey = exp2f(fmaf(zy_c[g], 1.4426950408889634f, -ref_l2e[g]));
   const T v = (T)(ey - Z);
   const int y = ids_c[g];
-  E[(int64_t)n * ld_e + y] = v;
-  ET[(int64_t)y * ld_et + n] = v;
+  E[tiled_index(n, y, ld_e)] = v;
+  ET[tiled_index(y, n, ld_et)] = v;
 }
 
 // ------------------------------------------------------------------ forward combine
@@ -485,7 +485,7 @@ __global__ void finalize_kernel(const float* seq_loss, const float* gterm, const
 template <class T>
 __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int cols, const int32_t* row_idx,
                                  const Ctrl* ctrl, int chunk_start, int dyn_rows, const ChunkDesc* desc, const float* row_scale,
-                                 T* dst, int64_t ld_dst, int rows_padded) {
+                                 T* dst, int64_t ld_dst, int rows_padded, bool dst_tiled) {
   __shared__ T tile[64][65];
   int rv = rows;
   if (dyn_rows) {
@@ -510,7 +510,7 @@ __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int col
   __syncthreads();
   for (int k = ty; k < 64; k += 4) {
     const int c = c0 + k, r = r0 + tx;
-    if (c < cols && r < rows_padded) dst[(int64_t)c * ld_dst + r] = tile[tx][k];
+    if (c < cols && r < rows_padded) dst[operand_index(dst_tiled, c, r, ld_dst)] = tile[tx][k];
   }
 }
 
@@ -552,6 +552,7 @@ struct Plan {
   int64_t R; int H, V, B, P; int dtype; size_t esz;
   int Tc, Vp, tiles_v, n_chunks;
   bool bwd;
+  bool tiled;            // bf16: the work buffers dS/E, dS^T/E^T, W^T, X^T are slab-tiled (hot kernel operands)
   bool stash;            // single-pass backward (forward keeps each chunk's unnormalised probabilities)
   int n_desc, max_len;   // stash: number of chunk records, promised bound on rows per sequence
   size_t off_ctrl, off_seq_len, off_cstart, off_row_map, off_ids_c, off_cpos, off_zy, off_lse_c, off_logp_c,
@@ -579,6 +580,7 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   p.tiles_v = p.Vp / kBM;
   p.n_chunks = (int)((b->R + tc - 1) / tc);
   p.bwd = bwd;
+  p.tiled = (b->dtype == RL_BF16);
   // Single-pass backward: bf16 hot-kernel shapes only, and only when the caller bounds the sequence length by a chunk.
   const int mode = prm ? prm->backward_mode : RL_BWD_AUTO;
   if (mode != RL_BWD_AUTO && mode != RL_BWD_RECOMPUTE && mode != RL_BWD_STASH) return RL_ERR_RANGE;
@@ -601,8 +603,9 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   p.off_part = take(sizeof(float4) * (size_t)p.tiles_v * (size_t)tc);
   p.off_wt = p.off_xt = p.off_ds = p.off_dst = 0;
   if (bwd) {
-    p.off_wt = take(p.esz * (size_t)b->H * (size_t)p.Vp);
-    p.off_xt = take(p.esz * (size_t)b->H * (size_t)tc);
+    const size_t Hp = ((size_t)b->H + 255) & ~(size_t)255;   // tiled layouts come in blocks of 256 rows
+    p.off_wt = take(p.esz * Hp * (size_t)p.Vp);
+    p.off_xt = take(p.esz * Hp * (size_t)tc);
     p.off_ds = take(p.esz * (size_t)tc * (size_t)p.Vp);
     p.off_dst = take(p.esz * (size_t)p.Vp * (size_t)tc);
   }
@@ -711,27 +714,27 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
   {
     ProfScope ps(RL_PROF_TRANSPOSE, s);
     dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
-    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp);
+    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp, p.tiled);
   }
   for (int ch = 0; ch < p.n_chunks; ++ch) {
     const int c0 = ch * p.Tc;
     {  // X^T chunk [H][Tc], gathered through row_map, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
-      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, nullptr, nullptr, XT, p.Tc, p.Tc);
+      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, nullptr, nullptr, XT, p.Tc, p.Tc, p.tiled);
     }
     {  // recompute logits, form dS and dS^T
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
       d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
-      EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V};
+      EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V, p.tiled};
       ProfScope ps(RL_PROF_GEMM_DS, s);
       launch_gemm<TuneLogits>(W, X, d, e, s);
     }
     {  // dX = dS W  : A = dS [Tc][Vp], B = W^T [H][Vp]
       GemmDims d{};
       d.M = p.Tc; d.N = p.H; d.K = p.Vp; d.lda = p.Vp; d.ldb = p.Vp;
-      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = TuneDX::kBand;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 1; d.group_m = TuneDX::kBand; d.a_tiled = d.b_tiled = p.tiled;
       EpiDX<T> e{q.row_map, dX, p.H, p.H, nullptr};
       ProfScope ps(RL_PROF_GEMM_DX, s);
       launch_gemm<TuneDX>(dS, WT, d, e, s);
@@ -739,7 +742,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
     {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
       GemmDims d{};
       d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
-      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = TuneDW::kBand;
+      d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = TuneDW::kBand; d.a_tiled = d.b_tiled = p.tiled;
       d.zero_if_empty = (ch == 0);
       EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
       ProfScope ps(RL_PROF_GEMM_DW, s);
@@ -766,7 +769,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     const int rows_per_block = 4;
     zero_masked_rows_kernel<T><<<(unsigned)((p.R + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(q.cpos, dX, p.R, p.H);
     dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
-    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp);
+    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp, p.tiled);
   }
   {
     ProfScope ps(RL_PROF_PREP, s);
@@ -801,17 +804,17 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     {  // X^T chunk scaled by -c/Z, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
-      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc);
+      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc, true);
     }
     {  // dX = diag(-c/Z) E' W  (A = E' [Tc][Vp], B = W^T [H][Vp]) and dW (+)= E'^T (diag(-c/Z) X)  (A = E'^T [Vp][Tc],
        // B = scaled X^T [H][Tc]) in one launch: dX alone has too few (long) tiles to fill its last round of CUs
       GemmDims dx{};
       dx.M = p.Tc; dx.N = p.H; dx.K = p.Vp; dx.lda = p.Vp; dx.ldb = p.Vp;
-      dx.chunk = chunk; dx.dyn = 1; dx.group_m = TuneDX::kBand;
+      dx.chunk = chunk; dx.dyn = 1; dx.group_m = TuneDX::kBand; dx.a_tiled = dx.b_tiled = 1;
       EpiDX<T> ex{q.row_map, dX, p.H, p.H, q.scale};
       GemmDims dw{};
       dw.M = p.V; dw.N = p.H; dw.K = p.Tc; dw.lda = p.Tc; dw.ldb = p.Tc;
-      dw.chunk = chunk; dw.dyn = 3; dw.zero_if_empty = (k == 0); dw.group_m = TuneDW::kBand;
+      dw.chunk = chunk; dw.dyn = 3; dw.zero_if_empty = (k == 0); dw.group_m = TuneDW::kBand; dw.a_tiled = dw.b_tiled = 1;
       EpiDW ew{out->d_weight, p.H, p.V, p.H, k > 0 ? 1 : 0};
       const int tn = (p.H + kBN - 1) / kBN;
       const int n1 = (((p.Tc + kBM - 1) / kBM) * tn + kXcds - 1) / kXcds * kXcds;
