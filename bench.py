@@ -22,10 +22,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 # HBM-side bytes (L2 <-> fabric; FETCH_SIZE x2.0 + WRITE_SIZE x1.0 after calibration against a plain 1 GiB copy)
-# of one full 32768-row launch of each contraction class on the default workload, from two rocprofv3 --pmc runs
-# whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
-MEASURED_TRAFFIC_7B_CHUNK32768 = {"gemm_fwd": 58.3e9 + 0.2e9, "gemm_ds": 53.5e9 + 20.9e9,
-                                  "gemm_dx": 57.3e9 + 0.2e9, "gemm_dw": 69.9e9 + 2.2e9}
+# of the largest launch of each contraction class on the default workload, from two rocprofv3 --pmc runs per
+# backward mode whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
+MEASURED_TRAFFIC_7B_CHUNK32768 = {
+    "stash": {"gemm_fwd": 63.7e9 + 23.8e9, "gemm_bwd": 151.1e9 + 2.4e9},
+    "recompute": {"gemm_fwd": 59.9e9 + 0.3e9, "gemm_ds": 53.5e9 + 23.9e9, "gemm_dx": 69.9e9 + 0.2e9, "gemm_dw": 71.3e9 + 2.2e9},
+}
 CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 8, "7b": 160, "long": 640, "32b": 768}   # ~10-30 s of oracle work
 
 
@@ -121,6 +123,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # launches per step that have rows to work on (the library launches a fixed upper bound of chunks; the rest return at once)
+    tc = a.chunk_rows or binding.lib().rl_default_chunk_rows()
+    stash = prof["gemm_bwd"][1] > 0
+    if stash:                                  # sequence-aligned chunks: greedy packing of whole sequences
+        real_chunks, rows = 1, 0
+        for n in b.lengths.tolist():
+            if rows > 0 and rows + n > tc:
+                real_chunks, rows = real_chunks + 1, 0
+            rows += n
+    else:
+        real_chunks = -(-b.T // tc)
     T = int(res.stats_dict()["n_tokens"])
     loss = float(res.loss.item())
     assert T == b.T and loss == loss, (T, b.T, loss)
@@ -152,12 +165,13 @@ def main():
         "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
         "roofline": {"bound": "mfma", "kernel": f"gemm_nt_bf16_kernel ({dom})", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": (MEASURED_TRAFFIC_7B_CHUNK32768.get(dom)
+                     "traffic": (MEASURED_TRAFFIC_7B_CHUNK32768["stash" if stash else "recompute"].get(dom)
                                  if (a.config == "7b" and a.len_div == 1 and a.layout == "padded"
                                      and (a.chunk_rows or 32768) == 32768) else None),
-                     "traffic_note": "bytes per full 32768-row launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
-                     "flops_per_full_launch": 2.0 * 32768 * cfg.H * cfg.V,
-                     "avg_launch_ms": dom_ms / max(dom_n, 1), "launches": int(dom_n)},
+                     "traffic_note": "HBM-side bytes of the largest launch of this class (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
+                     "launches_with_work": real_chunks * a.steps, "launches": int(dom_n),
+                     "avg_launch_ms": dom_ms / max(real_chunks * a.steps, 1),
+                     "flops_per_avg_launch": class_flops[dom] / real_chunks},
         "mfma_only_measured": {"burst_200ms": {"tflops": peak_burst[0], "shader_mhz": peak_burst[1]},
                                "sustained_1s": {"tflops": peak_sustained[0], "shader_mhz": peak_sustained[1]},
                                "roofline_frac_of_sustained": achieved / peak_sustained[0] if peak_sustained[0] > 0 else None},

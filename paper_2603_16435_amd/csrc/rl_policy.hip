@@ -590,7 +590,12 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   if (mode == RL_BWD_STASH && !can_stash) return RL_ERR_RANGE;
   p.stash = can_stash && mode != RL_BWD_RECOMPUTE;
   p.max_len = p.stash ? prm->max_seq_len : 0;
+  // chunk records: two consecutive chunks hold more than Tc rows, and every chunk but the last more than Tc - max_len
   p.n_desc = 2 * p.n_chunks + 1;
+  if (p.stash && p.max_len < tc) {
+    const int64_t alt = (b->R + (tc - p.max_len)) / (tc - p.max_len + 1) + 1;
+    if (alt < p.n_desc) p.n_desc = (int)alt;
+  }
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
   const size_t Rp = (size_t)rp + 256;
