@@ -208,6 +208,112 @@ def flow_loss(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, group_idx, 
 
 
 # --------------------------------------------------------------------------
+# objective variants (asymmetric clip, batch token-mean aggregation, sequence-level ratio,
+# length-normalised flow weight).  Written out separately from the base objectives above so that each
+# can be read against its own definition; with every option at its default they reduce to them.
+# --------------------------------------------------------------------------
+def grpo_loss_variant(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, clip_eps, kl_coef,
+                      clip_eps_high=None, aggregation="sequence", ratio_level="token"):
+    """Clipped-ratio objective with the options
+      clip_eps_high   upper clip bound 1 + clip_eps_high (lower stays 1 - clip_eps); None = symmetric
+      aggregation     "sequence": loss = (1/B) sum_i (1/|y_i|) sum_t l_t
+                      "token":    loss = (1/T) sum_i sum_t l_t, T = all counting tokens of the batch;
+                                  reported seq_loss_i = (B/T) sum_t l_t, so loss = mean_i seq_loss_i either way
+      ratio_level     "token":    rho_t = exp(logp_t - old_t) per token
+                      "sequence": one ratio per sequence, s_i = exp((1/|y_i|) sum_t (logp_t - old_t)), used for
+                                  every token of it: l_i = -min(s_i A_i, clip(s_i) A_i) + (kl_coef/|y_i|) sum_t k3_t
+                                  (sequence aggregation only).
+    The KL term is the per-token k3 estimator in every case.  Same return dict as grpo_loss; n_clip_* count
+    tokens (token level) or sequences (sequence level)."""
+    lp = widen(np.asarray(logp)); old = widen(np.asarray(old_logprob)); ref = widen(np.asarray(ref_logprob))
+    m = np.asarray(mask).astype(bool)
+    cu = np.asarray(cu_seqlens).astype(np.int64)
+    B = cu.size - 1
+    lo_c = 1.0 - clip_eps
+    hi_c = 1.0 + (clip_eps if clip_eps_high is None else clip_eps_high)
+    if aggregation not in ("sequence", "token") or ratio_level not in ("token", "sequence"):
+        raise ValueError("option")
+    if ratio_level == "sequence" and aggregation != "sequence":
+        raise ValueError("sequence-level ratio goes with sequence aggregation")
+    seg = [np.arange(cu[i], cu[i + 1])[m[cu[i]:cu[i + 1]]] for i in range(B)]
+    T = sum(r.size for r in seg)
+    seq_loss = np.zeros(B)
+    c = np.zeros(lp.shape[0])
+    n_hi = n_lo = 0
+    for i, rows in enumerate(seg):
+        n = rows.size
+        if n == 0:
+            continue
+        A = adv[i]
+        d = ref[rows] - lp[rows]
+        k3 = np.exp(d) - d - 1.0
+        dk3 = 1.0 - np.exp(d)                                  # d k3 / d logp
+        if ratio_level == "token":
+            rho = np.exp(lp[rows] - old[rows])
+            surr = np.minimum(rho * A, np.clip(rho, lo_c, hi_c) * A)
+            hi = (A > 0) & (rho > hi_c)
+            lo = (A < 0) & (rho < lo_c)
+            n_hi += int(hi.sum()); n_lo += int(lo.sum())
+            l = -surr + kl_coef * k3
+            g = -A * rho * ~(hi | lo) + kl_coef * dk3           # d l_t / d logp_t
+            if aggregation == "sequence":
+                seq_loss[i] = l.sum() / n
+                c[rows] = g / (B * n)
+            else:
+                seq_loss[i] = l.sum() * B / T
+                c[rows] = g / T
+        else:
+            s = np.exp((lp[rows] - old[rows]).sum() / n)
+            surr = min(s * A, min(max(s, lo_c), hi_c) * A)
+            hi = bool(A > 0 and s > hi_c)
+            lo = bool(A < 0 and s < lo_c)
+            n_hi += int(hi); n_lo += int(lo)
+            seq_loss[i] = -surr + kl_coef * k3.sum() / n
+            ds = 0.0 if (hi or lo) else -A * s / n               # d(-surr)/d logp_t: s depends on every token equally
+            c[rows] = (ds + kl_coef * dk3 / n) / B
+    return dict(loss=seq_loss.sum() / B, seq_loss=seq_loss, c=c, n_clip_hi=n_hi, n_clip_lo=n_lo)
+
+
+def flow_loss_variant(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, group_idx, log_z,
+                      clip_eps, beta, clip_eps_high=None, weight_norm="sum"):
+    """Flow-balance objective with the options
+      clip_eps_high   upper bound of the importance weight, 1 + clip_eps_high; None = symmetric
+      weight_norm     "sum":  w_i = clip(exp(sum_t (logp_t - old_t)))       (the base objective)
+                      "mean": w_i = clip(exp((1/|y_i|) sum_t (logp_t - old_t)))  (geometric-mean ratio)
+    w stays a constant (no gradient).  Same return dict as flow_loss."""
+    lp = widen(np.asarray(logp)); old = widen(np.asarray(old_logprob)); ref = widen(np.asarray(ref_logprob))
+    lz = widen(np.asarray(log_z))
+    g = np.asarray(group_idx).astype(np.int64)
+    m = np.asarray(mask).astype(bool)
+    cu = np.asarray(cu_seqlens).astype(np.int64)
+    B = cu.size - 1
+    if weight_norm not in ("sum", "mean"):
+        raise ValueError("option")
+    lo_b = np.log(1.0 - clip_eps)
+    hi_b = np.log(1.0 + (clip_eps if clip_eps_high is None else clip_eps_high))
+    seq_loss = np.zeros(B); w = np.zeros(B); delta = np.zeros(B)
+    c = np.zeros(lp.shape[0])
+    dz = np.zeros(lz.shape[0])
+    n_hi = n_lo = 0
+    for i in range(B):
+        rows = np.arange(cu[i], cu[i + 1])[m[cu[i]:cu[i + 1]]]
+        n = rows.size
+        if n == 0:
+            continue
+        log_ratio = (lp[rows] - old[rows]).sum()
+        if weight_norm == "mean":
+            log_ratio = log_ratio / n
+        w[i] = np.exp(min(max(log_ratio, lo_b), hi_b))
+        n_hi += int(log_ratio > hi_b); n_lo += int(log_ratio < lo_b)
+        delta[i] = lz[g[i]] + (lp[rows] - ref[rows]).sum() / n - beta * adv[i]
+        seq_loss[i] = w[i] * delta[i] ** 2
+        c[rows] = 2.0 * w[i] * delta[i] / (B * n)
+        dz[g[i]] += 2.0 * w[i] * delta[i] / B
+    return dict(loss=seq_loss.sum() / B, seq_loss=seq_loss, c=c, d_log_z=dz, w=w, delta=delta,
+                n_clip_hi=n_hi, n_clip_lo=n_lo)
+
+
+# --------------------------------------------------------------------------
 # backward through log-softmax and the LM head
 # --------------------------------------------------------------------------
 def lm_head_backward(hidden, weight, token_ids, mask, lse, c, want_dw=True):
@@ -240,13 +346,20 @@ GRPO, FLOW = 0, 1
 def policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx,
                         rewards, old_logprob, ref_logprob, log_z, P,
                         clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
-                        want_dw=True, want_grads=True, want_entropy=False):
+                        want_dw=True, want_grads=True, want_entropy=False, variant=None):
     """The whole path in the order of the problem statement: log-prob, per-sequence lengths,
-    group-relative advantage, loss + per-token coefficient, backward through the LM head."""
+    group-relative advantage, loss + per-token coefficient, backward through the LM head.
+    variant: optional dict of the keyword options of grpo_loss_variant / flow_loss_variant."""
     logp, lse = token_logprob(hidden, weight, token_ids, mask)
     seq_len = segment_lengths(mask, cu_seqlens)
     adv = group_advantage(rewards, group_idx, P, adv_eps, adv_std_ddof)
-    if objective == GRPO:
+    if objective == GRPO and variant:
+        out = grpo_loss_variant(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, clip_eps, kl_coef, **variant)
+        out["d_log_z"] = np.zeros(P)
+    elif objective == FLOW and variant:
+        out = flow_loss_variant(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, group_idx, log_z,
+                                clip_eps, beta, **variant)
+    elif objective == GRPO:
         out = grpo_loss(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, clip_eps, kl_coef)
         out["d_log_z"] = np.zeros(P)
     elif objective == FLOW:

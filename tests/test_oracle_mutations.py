@@ -37,6 +37,14 @@ MUTANTS = [
     ("backward: dW without the transpose", "dW += dS.T @ X[rows]", "dW += (X[rows].T @ dS).T * 0 + dS.T @ np.roll(X[rows], 1, axis=1)"),
     ("backward: masked rows leak", "rows = np.nonzero(m[s:e])[0] + s\n        if rows.size == 0:\n            continue\n        Z = X[rows] @ W.T\n        dS", "rows = np.arange(s, e)\n        if rows.size == 0:\n            continue\n        Z = X[rows] @ W.T\n        dS"),
     ("bf16 widening shifts by 15", "<< np.uint32(16)", "<< np.uint32(15)"),
+    ("variant: upper bound uses the lower epsilon", "hi_c = 1.0 + (clip_eps if clip_eps_high is None else clip_eps_high)", "hi_c = 1.0 + clip_eps"),
+    ("variant: token aggregation normalised by B n", "                c[rows] = g / T", "                c[rows] = g / (B * n)"),
+    ("variant: token aggregation seq_loss scale", "seq_loss[i] = l.sum() * B / T", "seq_loss[i] = l.sum() / T"),
+    ("variant: sequence ratio without the length normalisation", "s = np.exp((lp[rows] - old[rows]).sum() / n)", "s = np.exp((lp[rows] - old[rows]).sum())"),
+    ("variant: sequence ratio gradient ignores clipping", "ds = 0.0 if (hi or lo) else -A * s / n", "ds = -A * s / n"),
+    ("variant: sequence ratio KL not averaged", "seq_loss[i] = -surr + kl_coef * k3.sum() / n", "seq_loss[i] = -surr + kl_coef * k3.sum()"),
+    ("variant: flow mean weight not divided", "            log_ratio = log_ratio / n", "            log_ratio = log_ratio * 1.0"),
+    ("variant: flow upper bound", "hi_b = np.log(1.0 + (clip_eps if clip_eps_high is None else clip_eps_high))", "hi_b = np.log(1.0 + clip_eps)"),
 ]
 
 PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]

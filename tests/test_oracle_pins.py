@@ -399,3 +399,140 @@ def test_c_is_the_derivative_of_the_loss_in_logp():
         fm = orc.flow_loss(lp - e, old, ref, mask, cu, adv, g, lz, 0.2, 3.0)["delta"]
         num = ((f["w"] * fp ** 2).mean() - (f["w"] * fm ** 2).mean()) / (2 * h)
         assert f["c"][t] == pytest.approx(num, abs=1e-8)
+
+
+# ---------------------------------------------------------------------------
+# objective variants: reduce to the base objectives, closed forms per option, finite differences
+# ---------------------------------------------------------------------------
+def _variant_case(seed=10):
+    rng = np.random.default_rng(seed)
+    lens = [3, 1, 5, 2, 0, 4]
+    cu, R, mask, lp = _seqs(rng, lens)
+    old = lp + rng.normal(size=R) * 0.25            # wide enough that both clip branches occur
+    ref = lp + rng.normal(size=R) * 0.1
+    adv = np.array([0.7, -1.3, 0.4, 2.0, 1.0, -0.6])
+    g = np.array([0, 0, 1, 1, 2, 2]); lz = np.array([0.4, -0.9, 0.1])
+    return lens, cu, R, mask, lp, old, ref, adv, g, lz
+
+
+def test_variants_reduce_to_the_base_objectives():
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case()
+    a = orc.grpo_loss(lp, old, ref, mask, cu, adv, 0.2, 0.3)
+    b = orc.grpo_loss_variant(lp, old, ref, mask, cu, adv, 0.2, 0.3)
+    b2 = orc.grpo_loss_variant(lp, old, ref, mask, cu, adv, 0.2, 0.3, clip_eps_high=0.2)
+    for k in ("loss", "seq_loss", "c", "n_clip_hi", "n_clip_lo"):
+        np.testing.assert_allclose(a[k], b[k], rtol=0, atol=1e-15)
+        np.testing.assert_allclose(a[k], b2[k], rtol=0, atol=1e-15)
+    assert a["n_clip_hi"] > 0 and a["n_clip_lo"] > 0
+    f = orc.flow_loss(lp, old, ref, mask, cu, adv, g, lz, 0.2, 3.0)
+    fv = orc.flow_loss_variant(lp, old, ref, mask, cu, adv, g, lz, 0.2, 3.0)
+    for k in ("loss", "seq_loss", "c", "d_log_z", "w", "delta"):
+        np.testing.assert_allclose(f[k], fv[k], rtol=0, atol=1e-15)
+
+
+def test_asymmetric_clip_closed_forms():
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case()
+    B = len(lens); n = np.array(lens)
+    # rho = 1.25 everywhere, A > 0: clipped with eps_high = 0.2 (term -1.2 A, no gradient), not with 0.28 (term -1.25 A)
+    A = np.full(B, 1.5)
+    o = orc.grpo_loss_variant(lp, lp - math.log(1.25), lp, mask, cu, A, 0.2, 0.0, clip_eps_high=0.2)
+    assert o["loss"] == pytest.approx(-1.2 * 1.5 * 5 / 6, rel=1e-13) and np.all(o["c"] == 0)        # 5 of 6 sequences non-empty
+    o = orc.grpo_loss_variant(lp, lp - math.log(1.25), lp, mask, cu, A, 0.2, 0.0, clip_eps_high=0.28)
+    assert o["loss"] == pytest.approx(-1.25 * 1.5 * 5 / 6, rel=1e-13)
+    want = np.repeat(np.where(n > 0, -1.5 * 1.25 / (B * np.maximum(n, 1)), 0.0), lens)
+    np.testing.assert_allclose(o["c"], want, atol=1e-15)
+    # the lower bound is unaffected by eps_high: rho = 0.7, A < 0 -> term +0.8 |A|... (-min(0.7A, 0.8A) = -0.8A for A<0)
+    o = orc.grpo_loss_variant(lp, lp - math.log(0.7), lp, mask, cu, -A, 0.2, 0.0, clip_eps_high=0.5)
+    assert o["loss"] == pytest.approx(0.8 * 1.5 * 5 / 6, rel=1e-13) and np.all(o["c"] == 0)
+    # flow: the weight's upper bound moves, the lower does not
+    f = orc.flow_loss_variant(lp, lp - 1000.0, ref, mask, cu, adv, g, lz, 0.2, 3.0, clip_eps_high=0.5)
+    np.testing.assert_allclose(f["w"][n > 0], 1.5, atol=1e-15)
+    f = orc.flow_loss_variant(lp, lp + 1000.0, ref, mask, cu, adv, g, lz, 0.2, 3.0, clip_eps_high=0.5)
+    np.testing.assert_allclose(f["w"][n > 0], 0.8, atol=1e-15)
+
+
+def test_token_mean_aggregation():
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case()
+    B = len(lens); T = sum(lens)
+    seq = orc.grpo_loss_variant(lp, old, ref, mask, cu, adv, 0.2, 0.3)
+    tok = orc.grpo_loss_variant(lp, old, ref, mask, cu, adv, 0.2, 0.3, aggregation="token")
+    # same per-token terms, different weights: sequence mode weighs token t of sequence i by 1/(B n_i), token mode by 1/T
+    per_tok_seq = np.concatenate([seq["seq_loss"][i] * np.ones(lens[i]) for i in range(B)])      # mean l over the sequence
+    sums = np.array([seq["seq_loss"][i] * lens[i] for i in range(B)])                            # sum_t l_t per sequence
+    assert tok["loss"] == pytest.approx(sums.sum() / T, rel=1e-13)
+    np.testing.assert_allclose(tok["seq_loss"], sums * B / T, rtol=1e-13)
+    assert tok["loss"] == pytest.approx(tok["seq_loss"].mean(), rel=1e-13)
+    nrep = np.repeat(np.array(lens), lens)
+    np.testing.assert_allclose(tok["c"], seq["c"] * (B * nrep) / T, rtol=1e-13)
+    # equal lengths: both aggregations coincide
+    cu2 = np.array([0, 4, 8, 12]); m2 = np.ones(12, np.uint8)
+    a = orc.grpo_loss_variant(lp[:12], old[:12], ref[:12], m2, cu2, adv[:3], 0.2, 0.3)
+    b = orc.grpo_loss_variant(lp[:12], old[:12], ref[:12], m2, cu2, adv[:3], 0.2, 0.3, aggregation="token")
+    assert a["loss"] == pytest.approx(b["loss"], rel=1e-13)
+    np.testing.assert_allclose(a["c"], b["c"], rtol=1e-13)
+
+
+def test_sequence_level_ratio_closed_forms():
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case()
+    B = len(lens); n = np.array(lens)
+    # a constant per-token log-ratio makes the sequence ratio equal to the token ratio: same loss as the token-level form
+    for r in (1.1, 0.9, 1.5, 0.6):
+        a = orc.grpo_loss_variant(lp, lp - math.log(r), ref, mask, cu, adv, 0.2, 0.3)
+        b = orc.grpo_loss_variant(lp, lp - math.log(r), ref, mask, cu, adv, 0.2, 0.3, ratio_level="sequence")
+        assert a["loss"] == pytest.approx(b["loss"], rel=1e-13)
+        np.testing.assert_allclose(a["seq_loss"], b["seq_loss"], rtol=1e-12, atol=1e-15)
+        np.testing.assert_allclose(a["c"], b["c"], rtol=1e-12, atol=1e-16)
+    # geometric mean: log-ratios that cancel inside every sequence give s_i = 1 -> loss = -mean(A) over all B (+0 KL)
+    d = np.concatenate([x - x.mean() if x.size else x for x in np.split(np.resize([0.3, -0.1, 0.2], R).astype(float), cu[1:-1])])
+    o = orc.grpo_loss_variant(lp, lp - d, lp, mask, cu, adv, 0.2, 0.0, ratio_level="sequence")
+    assert o["loss"] == pytest.approx(-(adv[n > 0]).sum() / B, rel=1e-12)
+    np.testing.assert_allclose(o["c"], np.repeat(np.where(n > 0, -adv / (B * np.maximum(n, 1)), 0.0), lens), atol=1e-14)
+    # counts are per sequence
+    o = orc.grpo_loss_variant(lp, lp - math.log(2.0), lp, mask, cu, np.abs(adv), 0.2, 0.0, ratio_level="sequence")
+    assert o["n_clip_hi"] == 5 and o["n_clip_lo"] == 0 and np.all(o["c"] == 0)
+
+
+def test_flow_length_normalised_weight():
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case()
+    n = np.array(lens)
+    o = orc.flow_loss_variant(lp, old, ref, mask, cu, adv, g, lz, 0.2, 3.0, weight_norm="mean")
+    base = orc.flow_loss_variant(lp, old, ref, mask, cu, adv, g, lz, 0.2, 3.0)
+    np.testing.assert_allclose(o["delta"], base["delta"], atol=0)                  # only w changes
+    want = np.array([math.exp(min(max((lp - old)[cu[i]:cu[i + 1]].mean(), math.log(0.8)), math.log(1.2))) if lens[i] else 0.0 for i in range(len(lens))])
+    np.testing.assert_allclose(o["w"], want, rtol=1e-14)
+    np.testing.assert_allclose(o["seq_loss"], want * base["delta"] ** 2, rtol=1e-13)
+    # single-token sequences: sum and mean coincide
+    assert o["w"][1] == base["w"][1]
+    # a constant log-ratio r per token: mean gives exp(r) whatever the length, sum gives exp(n r)
+    o = orc.flow_loss_variant(lp, lp - 0.05, ref, mask, cu, adv, g, lz, 0.2, 3.0, weight_norm="mean")
+    np.testing.assert_allclose(o["w"][n > 0], math.exp(0.05), rtol=1e-14)
+
+
+@pytest.mark.parametrize("opts", [dict(clip_eps_high=0.35), dict(aggregation="token"), dict(ratio_level="sequence"),
+                                  dict(clip_eps_high=0.3, aggregation="token"), dict(clip_eps_high=0.1, ratio_level="sequence")])
+def test_variant_gradients_by_finite_differences(opts):
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case(seed=10)
+    o = orc.grpo_loss_variant(lp, old, ref, mask, cu, adv, 0.2, 0.25, **opts)
+    h = 1e-6
+    num = np.zeros(R)
+    for t in range(R):
+        e = np.zeros(R); e[t] = h
+        num[t] = (orc.grpo_loss_variant(lp + e, old, ref, mask, cu, adv, 0.2, 0.25, **opts)["loss"]
+                  - orc.grpo_loss_variant(lp - e, old, ref, mask, cu, adv, 0.2, 0.25, **opts)["loss"]) / (2 * h)
+    np.testing.assert_allclose(o["c"], num, rtol=2e-7, atol=1e-9)
+    assert o["n_clip_hi"] + o["n_clip_lo"] > 0                     # the case does exercise a switched-off branch
+
+
+def test_flow_variant_gradient_with_frozen_weight():
+    lens, cu, R, mask, lp, old, ref, adv, g, lz = _variant_case(seed=29)
+    for opts in (dict(weight_norm="mean"), dict(weight_norm="mean", clip_eps_high=0.4)):
+        o = orc.flow_loss_variant(lp, old, ref, mask, cu, adv, g, lz, 0.2, 3.0, **opts)
+        B = len(lens)
+        h = 1e-6
+        for t in range(R):
+            e = np.zeros(R); e[t] = h
+            dp = orc.flow_loss_variant(lp + e, old, ref, mask, cu, adv, g, lz, 0.2, 3.0, **opts)["delta"]
+            dm = orc.flow_loss_variant(lp - e, old, ref, mask, cu, adv, g, lz, 0.2, 3.0, **opts)["delta"]
+            num = (o["w"] * (dp ** 2 - dm ** 2)).sum() / B / (2 * h)          # w held at the base point
+            assert o["c"][t] == pytest.approx(num, rel=2e-7, abs=1e-9)
+
