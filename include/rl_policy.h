@@ -73,6 +73,9 @@ typedef enum rl_dtype { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
  *                    probabilities overflow beyond that and the loss comes back non-finite).
  *  RL_BWD_AUTO       RL_BWD_STASH when its conditions hold, else RL_BWD_RECOMPUTE.
  * Either way at most chunk_rows x V values are held at a time, never T x V. */
+typedef enum rl_aggregation { RL_AGG_SEQUENCE = 0, RL_AGG_TOKEN = 1 } rl_aggregation;
+typedef enum rl_ratio_level { RL_RATIO_TOKEN = 0, RL_RATIO_SEQUENCE = 1 } rl_ratio_level;
+typedef enum rl_weight_norm { RL_WNORM_SUM = 0, RL_WNORM_MEAN = 1 } rl_weight_norm;
 typedef enum rl_backward_mode { RL_BWD_AUTO = 0, RL_BWD_RECOMPUTE = 1, RL_BWD_STASH = 2 } rl_backward_mode;
 
 typedef struct rl_batch {
@@ -100,6 +103,13 @@ typedef struct rl_params {
   int32_t adv_std_ddof;         /* 0 (population std) or 1                               */
   int32_t chunk_rows;           /* rows of dS staged at once; 0 = library default.       */
                                 /* rounded up to a multiple of 256; sizes the workspace  */
+  float   clip_eps_high;        /* upper bound of the ratio / weight is 1 + clip_eps_high; 0 = clip_eps (symmetric) */
+  int32_t aggregation;          /* GRPO: RL_AGG_SEQUENCE (mean over sequences of the token mean) or         */
+                                /* RL_AGG_TOKEN (mean over all counting tokens of the batch; seq_loss[i]    */
+                                /* is then (B/T) sum_t l_t, so loss = mean_i seq_loss_i still holds)        */
+  int32_t ratio_level;          /* GRPO: RL_RATIO_TOKEN, or RL_RATIO_SEQUENCE = one ratio per sequence,     */
+                                /* exp(mean_t(logp_t - old_t)), clipped as a whole (sequence aggregation)   */
+  int32_t flow_weight_norm;     /* FLOW: weight from the RL_WNORM_SUM or RL_WNORM_MEAN of token log-ratios  */
   int32_t backward_mode;        /* rl_backward_mode; 0 = RL_BWD_AUTO                     */
   int32_t max_seq_len;          /* promise: no sequence has more counting rows than this; */
                                 /* 0 = no promise.  Needed by the single-pass backward.   */

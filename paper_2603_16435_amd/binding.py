@@ -31,6 +31,8 @@ class rl_batch(C.Structure):
 class rl_params(C.Structure):
     _fields_ = [("clip_eps", C.c_float), ("kl_coef", C.c_float), ("beta", C.c_float), ("adv_eps", C.c_float),
                 ("adv_std_ddof", C.c_int32), ("chunk_rows", C.c_int32),
+                ("clip_eps_high", C.c_float), ("aggregation", C.c_int32), ("ratio_level", C.c_int32),
+                ("flow_weight_norm", C.c_int32),
                 ("backward_mode", C.c_int32), ("max_seq_len", C.c_int32)]
 
 
@@ -233,20 +235,33 @@ class PolicyLossPlan:
         return self.res
 
 
+AGGREGATIONS = {"sequence": 0, "token": 1}
+RATIO_LEVELS = {"token": 0, "sequence": 1}
+WEIGHT_NORMS = {"sum": 0, "mean": 1}
+
+
+def _enum(table, v):
+    return table[v] if isinstance(v, str) else int(v)
+
+
 def make_params(clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0, chunk_rows=0,
-                backward_mode="auto", max_seq_len=0) -> rl_params:
-    mode = BACKWARD_MODES[backward_mode] if isinstance(backward_mode, str) else int(backward_mode)
-    return rl_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, mode, int(max_seq_len))
+                backward_mode="auto", max_seq_len=0, clip_eps_high=0.0, aggregation="sequence",
+                ratio_level="token", flow_weight_norm="sum") -> rl_params:
+    return rl_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows,
+                     float(clip_eps_high or 0.0), _enum(AGGREGATIONS, aggregation), _enum(RATIO_LEVELS, ratio_level),
+                     _enum(WEIGHT_NORMS, flow_weight_norm), _enum(BACKWARD_MODES, backward_mode), int(max_seq_len))
 
 
 def rl_policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards,
                            old_logprob, ref_logprob, log_z=None, P: Optional[int] = None,
                            clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
-                           chunk_rows=0, backward=True, backward_mode="auto", max_seq_len=0) -> LossResult:
+                           chunk_rows=0, backward=True, backward_mode="auto", max_seq_len=0, clip_eps_high=0.0,
+                           aggregation="sequence", ratio_level="token", flow_weight_norm="sum") -> LossResult:
     """One pass of the whole path.  `objective` is "grpo" | "flow" (or the enum value)."""
     obj = OBJECTIVES[objective] if isinstance(objective, str) else int(objective)
     b = make_batch(hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards, old_logprob, ref_logprob, log_z, P)
-    prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, backward_mode, max_seq_len)
+    prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, backward_mode, max_seq_len,
+                      clip_eps_high, aggregation, ratio_level, flow_weight_norm)
     plan = PolicyLossPlan(b, prm, hidden.device, hidden.dtype, backward)
     return plan.run(obj)
 

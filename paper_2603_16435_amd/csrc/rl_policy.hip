@@ -379,11 +379,18 @@ __global__ void lse_combine_kernel(const float4* part, int ldp, int tiles_v, con
 }
 
 // ------------------------------------------------------------------ loss
+struct LossOpts {
+  float clip_lo, clip_hi;   // ratio / weight kept inside [1 - clip_lo, 1 + clip_hi]
+  float kl_coef, beta;
+  int token_agg;            // GRPO: loss = (1/T) sum of all token terms instead of the mean of per-sequence means
+  int seq_ratio;            // GRPO: one ratio per sequence, exp(mean_t (logp - old))
+  int w_mean;               // FLOW: weight from the mean instead of the sum of the token log-ratios
+};
+
 // One workgroup per sequence over its compact rows [cstart[i], cstart[i+1]).
 __global__ void seq_loss_kernel(int objective, const float* logp_c, const float* old_lp, const float* ref_lp,
                                 const int32_t* row_map, const int32_t* cstart, const float* adv,
-                                const int32_t* group_idx, const float* log_z, int B,
-                                float clip_eps, float kl_coef, float beta,
+                                const int32_t* group_idx, const float* log_z, int B, LossOpts o, const Ctrl* ctrl,
                                 float* seq_loss, float* gterm, float* c_c, float* coeff_out, rl_stats* stats,
                                 const ChunkDesc* desc) {
   __shared__ double sh[16];
@@ -400,8 +407,12 @@ __global__ void seq_loss_kernel(int objective, const float* logp_c, const float*
     return;
   }
   const float A = adv[i];
+  const double Ad = (double)A;
   const double inv_bn = 1.0 / ((double)B * (double)n);
-  if (objective == RL_OBJ_GRPO) {
+  const double lo_c = 1.0 - (double)o.clip_lo, hi_c = 1.0 + (double)o.clip_hi;
+  if (objective == RL_OBJ_GRPO && !o.seq_ratio) {
+    // weight of a token term in the loss: 1/(B n_i) (mean of per-sequence means) or 1/T (mean over all tokens)
+    const double wt = o.token_agg ? 1.0 / (double)ctrl->n_real : inv_bn;
     double acc = 0.0; int hi = 0, lo = 0;
     for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
       const int r = row_map[k];
@@ -410,26 +421,53 @@ __global__ void seq_loss_kernel(int objective, const float* logp_c, const float*
       const double rho = exp(lp - (double)old_lp[r]);
       const double dd = (double)ref_lp[r] - lp;
       const double ed = exp(dd);
-      const double lo_c = 1.0 - (double)clip_eps, hi_c = 1.0 + (double)clip_eps;
       const double rc = fmin(fmax(rho, lo_c), hi_c);
-      const double Ad = (double)A;
-      const double l = -fmin(rho * Ad, rc * Ad) + (double)kl_coef * (ed - dd - 1.0);
+      const double l = -fmin(rho * Ad, rc * Ad) + (double)o.kl_coef * (ed - dd - 1.0);
       const bool chi = (A > 0.f) && (rho > hi_c);
       const bool clo = (A < 0.f) && (rho < lo_c);
       hi += chi; lo += clo;
-      const double g = ((chi || clo) ? 0.0 : -Ad * rho) + (double)kl_coef * (1.0 - ed);
-      const float ct = (float)(g * inv_bn);
+      const double g = ((chi || clo) ? 0.0 : -Ad * rho) + (double)o.kl_coef * (1.0 - ed);
+      const float ct = (float)(g * wt);
       c_c[k] = ct;
       if (coeff_out) coeff_out[r] = ct;
       acc += l;
     }
     const double tot = block_sum(acc, sh);
-    for (int o = 32; o > 0; o >>= 1) { hi += __shfl_down(hi, o); lo += __shfl_down(lo, o); }
+    for (int q = 32; q > 0; q >>= 1) { hi += __shfl_down(hi, q); lo += __shfl_down(lo, q); }
     if ((threadIdx.x & 63) == 0) { if (hi) atomicAdd(&sh_hi, hi); if (lo) atomicAdd(&sh_lo, lo); }
     __syncthreads();
     if (threadIdx.x == 0) {
-      seq_loss[i] = (float)(tot / n); gterm[i] = 0.f;
+      // token aggregation reports (B/T) sum_t l_t, so that loss = mean_i seq_loss_i in both aggregations
+      seq_loss[i] = (float)(o.token_agg ? tot * wt * (double)B : tot / n); gterm[i] = 0.f;
       if (stats) { if (sh_hi) atomicAdd(&stats->n_clip_hi, sh_hi); if (sh_lo) atomicAdd(&stats->n_clip_lo, sh_lo); }
+    }
+  } else if (objective == RL_OBJ_GRPO) {
+    // sequence-level ratio s = exp(mean_t (logp - old)): first the mean and the KL sum, then the coefficients
+    double s_old = 0.0, s_kl = 0.0;
+    for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
+      const int r = row_map[k];
+      const double lp = (double)logp_c[k];
+      const double dd = (double)ref_lp[r] - lp;
+      s_old += lp - (double)old_lp[r];
+      s_kl += exp(dd) - dd - 1.0;
+    }
+    const double t_old = block_sum(s_old, sh);
+    const double t_kl = block_sum(s_kl, sh);
+    const double sr = exp(t_old / n);
+    const double rc = fmin(fmax(sr, lo_c), hi_c);
+    const bool chi = (A > 0.f) && (sr > hi_c);
+    const bool clo = (A < 0.f) && (sr < lo_c);
+    const double ds = (chi || clo) ? 0.0 : -Ad * sr;               // d(-surrogate)/d(mean log-ratio)
+    for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
+      const int r = row_map[k];
+      const double dd = (double)ref_lp[r] - (double)logp_c[k];
+      const float ct = (float)((ds + (double)o.kl_coef * (1.0 - exp(dd))) * inv_bn);
+      c_c[k] = ct;
+      if (coeff_out) coeff_out[r] = ct;
+    }
+    if (threadIdx.x == 0) {
+      seq_loss[i] = (float)(-fmin(sr * Ad, rc * Ad) + (double)o.kl_coef * t_kl / n); gterm[i] = 0.f;
+      if (stats) { if (chi) atomicAdd(&stats->n_clip_hi, 1); if (clo) atomicAdd(&stats->n_clip_lo, 1); }
     }
   } else {
     double s_ref = 0.0, s_old = 0.0;
@@ -440,10 +478,11 @@ __global__ void seq_loss_kernel(int objective, const float* logp_c, const float*
       s_old += (double)(lp - old_lp[r]);
     }
     const double t_ref = block_sum(s_ref, sh);
-    const double t_old = block_sum(s_old, sh);
-    const double lo_b = log1p(-(double)clip_eps), hi_b = log1p((double)clip_eps);
+    double t_old = block_sum(s_old, sh);
+    if (o.w_mean) t_old /= n;
+    const double lo_b = log1p(-(double)o.clip_lo), hi_b = log1p((double)o.clip_hi);
     const double w = exp(fmin(fmax(t_old, lo_b), hi_b));
-    const double delta = (double)log_z[group_idx[i]] + t_ref / n - (double)beta * (double)A;
+    const double delta = (double)log_z[group_idx[i]] + t_ref / n - (double)o.beta * Ad;
     const float ct = (float)(2.0 * w * delta * inv_bn);
     for (int k = a + threadIdx.x; k < b; k += blockDim.x) {
       c_c[k] = ct;
@@ -756,6 +795,17 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
   }
 }
 
+static LossOpts loss_opts(const rl_params* prm) {
+  LossOpts o;
+  o.clip_lo = prm->clip_eps;
+  o.clip_hi = prm->clip_eps_high > 0.f ? prm->clip_eps_high : prm->clip_eps;
+  o.kl_coef = prm->kl_coef; o.beta = prm->beta;
+  o.token_agg = prm->aggregation == RL_AGG_TOKEN;
+  o.seq_ratio = prm->ratio_level == RL_RATIO_SEQUENCE;
+  o.w_mean = prm->flow_weight_norm == RL_WNORM_MEAN;
+  return o;
+}
+
 // Single-pass variant of forward + loss + backward (bf16 hot kernels): chunks are made of whole
 // sequences, so each chunk's loss coefficients are known as soon as its forward is; the forward
 // keeps the chunk's unnormalised probabilities E (and E^T) and the backward contractions run on
@@ -802,7 +852,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     {
       ProfScope ps(RL_PROF_LOSS, s);
       seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
-                                         b->group_idx, b->log_z, p.B, prm->clip_eps, prm->kl_coef, prm->beta,
+                                         b->group_idx, b->log_z, p.B, loss_opts(prm), q.ctrl,
                                          q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats, dk);
       stash_patch_kernel<T><<<(p.Tc + 255) / 256, 256, 0, s>>>(dk, q.ids_c, q.zy, q.ref, q.zsum, q.c_c, q.scale, E, p.Vp, ET, p.Tc);
     }
@@ -874,7 +924,7 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 102; }
+int32_t rl_version(void) { return 103; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
 
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
@@ -946,6 +996,12 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   if (!(prm->clip_eps > 0.f && prm->clip_eps < 1.f)) return RL_ERR_RANGE;
   if (prm->adv_std_ddof != 0 && prm->adv_std_ddof != 1) return RL_ERR_RANGE;
   if (!(prm->adv_eps >= 0.f)) return RL_ERR_RANGE;
+  if (!(prm->clip_eps_high >= 0.f)) return RL_ERR_RANGE;
+  if ((prm->aggregation != RL_AGG_SEQUENCE && prm->aggregation != RL_AGG_TOKEN) ||
+      (prm->ratio_level != RL_RATIO_TOKEN && prm->ratio_level != RL_RATIO_SEQUENCE) ||
+      (prm->flow_weight_norm != RL_WNORM_SUM && prm->flow_weight_norm != RL_WNORM_MEAN))
+    return RL_ERR_RANGE;
+  if (prm->ratio_level == RL_RATIO_SEQUENCE && prm->aggregation == RL_AGG_TOKEN) return RL_ERR_RANGE;
   const bool bwd = out->d_hidden || out->d_weight;
   if (bwd && (!out->d_hidden || !out->d_weight)) return RL_ERR_NULL;
   Plan p;
@@ -976,7 +1032,7 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   {
   ProfScope ps(RL_PROF_LOSS, s);
   seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
-                                     b->group_idx, b->log_z, p.B, prm->clip_eps, prm->kl_coef, prm->beta,
+                                     b->group_idx, b->log_z, p.B, loss_opts(prm), q.ctrl,
                                      q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats, nullptr);
   finalize_kernel<<<1, 1024, 0, s>>>(q.seq_loss, q.gterm, b->group_idx, q.seq_len, p.B, p.P, objective, q.ctrl,
                                     out->loss, out->d_log_z, out->seq_loss);

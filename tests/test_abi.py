@@ -103,6 +103,9 @@ def test_null_and_range_errors_are_rejected_on_the_host(lib):
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 1, C.byref(out), None, 0, None) == 1      # FLOW needs log_z
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(clip_eps=1.5)), 0, C.byref(out), None, 0, None) == 4
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(adv_std_ddof=2)), 0, C.byref(out), None, 0, None) == 4
+    for bad in (dict(clip_eps_high=-0.1), dict(aggregation=2), dict(ratio_level=3), dict(flow_weight_norm=-1),
+                dict(ratio_level="sequence", aggregation="token")):
+        assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(**bad)), 0, C.byref(out), None, 0, None) == 4, bad
     out.d_hidden = fake                                                                                   # d_weight missing
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), None, 0, None) == 1
     out.d_weight = fake

@@ -165,6 +165,63 @@ def test_stash_mode_no_tokens_and_broken_promise():
     assert res.stats_dict()["n_seq_too_long"] == 0
 
 
+# --------------------------------------------------------------------------- objective variants
+# (oracle option dict, library keyword arguments) per objective
+VARIANTS = {
+    "grpo": [(dict(clip_eps_high=0.35), dict(clip_eps_high=0.35)),
+             (dict(aggregation="token"), dict(aggregation="token")),
+             (dict(ratio_level="sequence"), dict(ratio_level="sequence")),
+             (dict(clip_eps_high=0.1, aggregation="token"), dict(clip_eps_high=0.1, aggregation="token")),
+             (dict(clip_eps_high=0.3, ratio_level="sequence"), dict(clip_eps_high=0.3, ratio_level="sequence"))],
+    "flow": [(dict(clip_eps_high=0.5), dict(clip_eps_high=0.5)),
+             (dict(weight_norm="mean"), dict(flow_weight_norm="mean")),
+             (dict(weight_norm="mean", clip_eps_high=0.05), dict(flow_weight_norm="mean", clip_eps_high=0.05))],
+}
+
+
+@pytest.mark.parametrize("objective", ["grpo", "flow"])
+def test_objective_variants_f32(objective):
+    # wide old/current noise so that both clip branches, both advantage signs and both weight bounds occur
+    b = synth.make_rollouts("tiny", "cuda", "padded", noise=0.3)
+    for o_opts, g_opts in VARIANTS[objective]:
+        ref = run_oracle(b, objective, variant=o_opts)
+        res = run_gpu(b, objective, **g_opts)
+        err = compare_all(b, res, ref, **F32_TOL)
+        st = res.stats_dict()
+        assert abs(st["n_clip_hi"] - ref["n_clip_hi"]) <= 1 and abs(st["n_clip_lo"] - ref["n_clip_lo"]) <= 1
+        _say("  variant", objective, o_opts, err, "clipped", st["n_clip_hi"], st["n_clip_lo"])
+
+
+def test_sequence_level_variants_with_clipped_sequences():
+    # per-sequence shifts of the old log-probs push whole sequences over either clip bound, which the per-token
+    # noise alone never does for a geometric-mean ratio
+    b = synth.make_rollouts("tiny", "cuda", "packed", noise=0.3)
+    cu = b.cu_seqlens.cpu().numpy()
+    for i, sh in enumerate([0.5, -0.5, 0.3, -0.3, 0.0, 0.25, -0.25, 0.1]):
+        b.old_logprob[int(cu[i]):int(cu[i + 1])] += sh
+    ref = run_oracle(b, "grpo", variant=dict(ratio_level="sequence"))
+    res = run_gpu(b, "grpo", ratio_level="sequence")
+    compare_all(b, res, ref, **F32_TOL)
+    st = res.stats_dict()
+    assert (st["n_clip_hi"], st["n_clip_lo"]) == (ref["n_clip_hi"], ref["n_clip_lo"]) and st["n_clip_hi"] + st["n_clip_lo"] >= 2
+    ref = run_oracle(b, "flow", variant=dict(weight_norm="mean", clip_eps_high=0.4))
+    res = run_gpu(b, "flow", flow_weight_norm="mean", clip_eps_high=0.4)
+    compare_all(b, res, ref, **F32_TOL)
+    st = res.stats_dict()
+    assert (st["n_clip_hi"], st["n_clip_lo"]) == (ref["n_clip_hi"], ref["n_clip_lo"]) and st["n_clip_hi"] >= 1 and st["n_clip_lo"] >= 1
+
+
+@pytest.mark.parametrize("mode", ["recompute", "stash"])
+def test_objective_variants_bf16_both_backward_modes(mode):
+    b = synth.make_rollouts("small", "cuda", "padded", len_div=16, noise=0.3)
+    for objective in ("grpo", "flow"):
+        for o_opts, g_opts in VARIANTS[objective][:3]:
+            ref = run_oracle(b, objective, variant=o_opts)
+            res = run_gpu(b, objective, chunk_rows=1024, mode=mode, **g_opts)
+            err = compare_all(b, res, ref, **BF16_TOL)
+            _say("  variant", objective, mode, o_opts, err)
+
+
 def test_out_of_range_token_ids_are_masked_and_counted():
     b = _edge_batch("bf16", 64, 512, [6, 4, 7, 3], P=2, G=2, layout="packed")
     bad_rows = [1, 9, 19]
