@@ -189,6 +189,28 @@ rl_status rl_profile_read(rl_profile* out);
 int32_t rl_version(void);
 int32_t rl_default_chunk_rows(void);
 
+/* The log-Z head: the step that produces rl_batch.log_z for the flow-balance objective (the problem
+ * statement takes "per-prompt log Z" as given; reading: a two-layer MLP over the mean of the prompt's
+ * hidden states, log_z[p] = w2 . gelu(W1 mean_t(h_t) + b1) + b2 with the exact (erf) GELU; the hidden
+ * states are constants).  All pointers are device pointers.
+ *   prompt_hidden [rows, H] in `dtype` (rl_dtype), row-major; prompt p owns rows [cu_prompt[p], cu_prompt[p+1])
+ *                 (cu_prompt: P+1 int32; an empty prompt pools to zero; ranges are clamped to [0, rows]);
+ *   W1 [M, H] f32 row-major (16-byte aligned), b1 [M], w2 [M], b2 [1] f32; H must be a multiple of 4;
+ *   log_z [P] f32, overwritten.
+ * The workspace (rl_logz_head_workspace_bytes, 256-byte aligned, caller-owned) keeps the pooled states and
+ * the hidden-layer activations between the two calls: rl_logz_head_backward must be given the workspace of
+ * the matching forward call, unmodified.  Backward: from d_log_z [P] (rl_outputs.d_log_z) it overwrites
+ * dW1 [M, H], db1 [M], dw2 [M], db2 [1] (f32).  Neither call allocates or synchronises; both enqueue on
+ * `stream`.  Errors as for the other entry points (RL_ERR_NULL / SHAPE / DTYPE / WORKSPACE / HIP). */
+rl_status rl_logz_head_workspace_bytes(int32_t P, int32_t H, int32_t M, size_t* bytes);
+rl_status rl_logz_head_forward(const void* prompt_hidden, int32_t dtype, int64_t rows, int32_t H,
+                               const int32_t* cu_prompt, int32_t P, const float* W1, const float* b1,
+                               const float* w2, const float* b2, int32_t M, float* log_z,
+                               void* workspace, size_t workspace_bytes, void* stream);
+rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int32_t M, const float* w2,
+                                float* dW1, float* db1, float* dw2, float* db2,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* Benchmark aid: runs a pure bf16 MFMA issue loop (v_mfma_f32_32x32x16_bf16, 16 independent
  * accumulators per wavefront, four wavefronts per CU, no memory traffic) for about `millis` ms on
  * `stream`, SYNCHRONISES on it, and returns the rate it reached and the shader clock it ran at.  This is

@@ -91,6 +91,14 @@ def lib() -> C.CDLL:
         L.rl_profile_read.restype = C.c_int
         L.rl_measure_mfma_peak.argtypes = [C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.rl_measure_mfma_peak.restype = C.c_int
+        L.rl_logz_head_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+        L.rl_logz_head_workspace_bytes.restype = C.c_int
+        L.rl_logz_head_forward.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rl_logz_head_forward.restype = C.c_int
+        L.rl_logz_head_backward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rl_logz_head_backward.restype = C.c_int
         L.rl_version.restype = C.c_int32
         L.rl_default_chunk_rows.restype = C.c_int32
         _lib = L
@@ -283,3 +291,38 @@ def rl_measure_mfma_peak(millis: int = 200, device="cuda:0"):
     t, m = C.c_double(0), C.c_double(0)
     _check(lib().rl_measure_mfma_peak(millis, buf.data_ptr(), buf.numel(), _stream_handle(), C.byref(t), C.byref(m)))
     return t.value, m.value
+
+
+# ------------------------------------------------------------------ log-Z head
+def rl_logz_head_forward(prompt_hidden, cu_prompt, W1, b1, w2, b2, workspace=None):
+    """log_z[P] = w2 . gelu(W1 mean(prompt rows) + b1) + b2.  Returns (log_z, workspace); hand the workspace to
+    rl_logz_head_backward unchanged."""
+    dev = prompt_hidden.device
+    rows, H = prompt_hidden.shape
+    P = cu_prompt.numel() - 1
+    M = W1.shape[0]
+    assert prompt_hidden.is_contiguous() and W1.is_contiguous() and W1.dtype == torch.float32 and W1.shape[1] == H
+    assert cu_prompt.dtype == torch.int32 and b1.dtype == w2.dtype == b2.dtype == torch.float32
+    need = C.c_size_t(0)
+    _check(lib().rl_logz_head_workspace_bytes(P, H, M, C.byref(need)))
+    ws = workspace if workspace is not None else _workspace(need.value, dev)
+    log_z = torch.empty(P, dtype=torch.float32, device=dev)
+    _check(lib().rl_logz_head_forward(prompt_hidden.data_ptr(), _dtype_code(prompt_hidden), rows, H, cu_prompt.data_ptr(), P,
+                                      W1.data_ptr(), b1.data_ptr(), w2.data_ptr(), b2.data_ptr(), M, log_z.data_ptr(),
+                                      ws.data_ptr(), ws.numel(), _stream_handle()))
+    return log_z, ws
+
+
+def rl_logz_head_backward(d_log_z, w2, H, workspace):
+    """Parameter gradients (dW1[M,H], db1[M], dw2[M], db2[1]) from d_log_z[P] and the forward's workspace."""
+    dev = d_log_z.device
+    P, M = d_log_z.numel(), w2.numel()
+    assert d_log_z.dtype == torch.float32 and w2.dtype == torch.float32
+    dW1 = torch.empty(M, H, dtype=torch.float32, device=dev)
+    db1 = torch.empty(M, dtype=torch.float32, device=dev)
+    dw2 = torch.empty(M, dtype=torch.float32, device=dev)
+    db2 = torch.empty(1, dtype=torch.float32, device=dev)
+    _check(lib().rl_logz_head_backward(d_log_z.data_ptr(), P, H, M, w2.data_ptr(), dW1.data_ptr(), db1.data_ptr(), dw2.data_ptr(),
+                                       db2.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_handle()))
+    return dW1, db1, dw2, db2
+

@@ -21,6 +21,7 @@
 
 #include "../../include/rl_policy.h"
 #include "epilogues.h"
+#include "logz_head.h"
 #include "gemm_nt.h"
 
 namespace rlk {
@@ -924,7 +925,7 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 103; }
+int32_t rl_version(void) { return 104; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
 
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
@@ -1041,6 +1042,70 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
     if (p.dtype == RL_BF16) run_backward<bf16_t>(b, p, q, out->d_hidden, out->d_weight, s);
     else run_backward<float>(b, p, q, out->d_hidden, out->d_weight, s);
   }
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+// ------------------------------------------------------------------ log-Z head
+static rl_status logz_check(int32_t P, int32_t H, int32_t M) {
+  if (P < 1 || H < 1 || M < 1 || P > (1 << 20) || (H % 4) != 0) return RL_ERR_SHAPE;
+  return RL_OK;
+}
+
+rl_status rl_logz_head_workspace_bytes(int32_t P, int32_t H, int32_t M, size_t* bytes) {
+  if (!bytes) return RL_ERR_NULL;
+  rl_status st = logz_check(P, H, M);
+  if (st != RL_OK) return st;
+  *bytes = logz_plan(P, H, M).total;
+  return RL_OK;
+}
+
+rl_status rl_logz_head_forward(const void* prompt_hidden, int32_t dtype, int64_t rows, int32_t H,
+                               const int32_t* cu_prompt, int32_t P, const float* W1, const float* b1,
+                               const float* w2, const float* b2, int32_t M, float* log_z,
+                               void* ws, size_t ws_bytes, void* stream) {
+  if (!prompt_hidden || !cu_prompt || !W1 || !b1 || !w2 || !b2 || !log_z) return RL_ERR_NULL;
+  if (dtype != RL_F32 && dtype != RL_BF16) return RL_ERR_DTYPE;
+  rl_status st = logz_check(P, H, M);
+  if (st != RL_OK) return st;
+  if (rows < 0) return RL_ERR_SHAPE;
+  const LogzPlan q = logz_plan(P, H, M);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < q.total) return RL_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(W1) & 15)) return RL_ERR_SHAPE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  float* pooled = (float*)(w + q.off_pooled); float* a = (float*)(w + q.off_a); float* g = (float*)(w + q.off_g);
+  dim3 gp(P, (H + 255) / 256);
+  if (dtype == RL_BF16) logz_pool_kernel<bf16_t><<<gp, 256, 0, s>>>(static_cast<const bf16_t*>(prompt_hidden), rows, H, cu_prompt, pooled);
+  else logz_pool_kernel<float><<<gp, 256, 0, s>>>(static_cast<const float*>(prompt_hidden), rows, H, cu_prompt, pooled);
+  // hidden layer as one NT contraction: A = W1 [M][H], B = pooled [P][H]; prompts in groups of one tile column
+  for (int p0 = 0; p0 < P; p0 += kBN) {
+    const int np = P - p0 < kBN ? P - p0 : kBN;
+    GemmDims d{};
+    d.M = M; d.N = np; d.K = H; d.lda = H; d.ldb = H; d.group_m = 1;
+    EpiMlpHidden e{b1, a + (int64_t)p0 * M, g + (int64_t)p0 * M, M, np};
+    launch_generic<float, EpiMlpHidden>(W1, pooled + (int64_t)p0 * H, d, e, (M + kBM - 1) / kBM, s);
+  }
+  logz_out_kernel<<<P, 256, 0, s>>>(g, w2, b2, M, log_z);
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int32_t M, const float* w2,
+                                float* dW1, float* db1, float* dw2, float* db2,
+                                void* ws, size_t ws_bytes, void* stream) {
+  if (!d_log_z || !w2 || !dW1 || !db1 || !dw2 || !db2) return RL_ERR_NULL;
+  rl_status st = logz_check(P, H, M);
+  if (st != RL_OK) return st;
+  const LogzPlan q = logz_plan(P, H, M);
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < q.total) return RL_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  unsigned char* w = static_cast<unsigned char*>(ws);
+  float* pooled = (float*)(w + q.off_pooled); float* a = (float*)(w + q.off_a); float* g = (float*)(w + q.off_g);
+  float* da = (float*)(w + q.off_da);
+  logz_bwd_vec_kernel<<<(M + 255) / 256, 256, 0, s>>>(d_log_z, a, g, w2, P, M, da, db1, dw2, db2);
+  dim3 gw((H + 255) / 256, M);
+  logz_bwd_w1_kernel<<<gw, 256, 0, s>>>(da, pooled, P, M, H, dW1);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 
