@@ -61,6 +61,47 @@ def cpu_baseline(name: str, objective: str):
                       f"full H={c.H} V={c.V}, fwd+bwd in float64, {dt:.1f} s"}
 
 
+def bench_logz_head(a, dev):
+    """The log-Z head of the same configuration: P prompts of U[128,1024] hidden-state rows, M = H, forward + backward."""
+    import numpy as np
+    import torch
+    from paper_2603_16435_amd import binding, synth
+    cfg = synth.CONFIGS[a.config]
+    P, H, M = cfg.P, cfg.H, cfg.H
+    g = torch.Generator().manual_seed(cfg.seed)
+    lens = torch.randint(128, 1025, (P,), generator=g)
+    cu = torch.cat([torch.zeros(1, dtype=torch.int64), lens.cumsum(0)]).to(torch.int32).to(dev)
+    rows = int(lens.sum())
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    X = torch.randn(rows, H, generator=g).to(dt).to(dev)
+    W1 = (torch.randn(M, H, generator=g) / np.sqrt(H)).to(dev); b1 = torch.zeros(M, device=dev)
+    w2 = (torch.randn(M, generator=g) / np.sqrt(M)).to(dev); b2 = torch.zeros(1, device=dev)
+    d = torch.randn(P, generator=g).to(dev)
+    _, ws = binding.rl_logz_head_forward(X, cu, W1, b1, w2, b2)
+
+    def step():
+        binding.rl_logz_head_forward(X, cu, W1, b1, w2, b2, workspace=ws)
+        binding.rl_logz_head_backward(d, w2, H, ws)
+    for _ in range(max(a.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    steps = max(a.steps, 20)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    # bytes the head must move: prompt rows once, W1 read once, dW1 written once (activations are a few hundred KB)
+    algo = rows * H * X.element_size() + 4.0 * M * H + 4.0 * M * H
+    out = {"metric": "log-Z head forward+backward, prompts/s", "value": P / sec, "unit": "prompts/s", "n_gpus": 1, "steps": steps,
+           "warmup": max(a.warmup, 1), "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"log-Z head of {a.config}: P={P} prompts, {rows} prompt rows, H={H}, hidden units M={M}, {cfg.dtype} states, f32 parameters"},
+           "roofline": {"bound": "hbm", "achieved": algo / sec / 1e9, "peak": 8000.0, "unit": "GB/s", "frac": algo / sec / 8e12, "traffic": None,
+                        "note": "five small launches per step plus host-side marshalling: launch-latency-bound at this size (W1 and dW1 are 51 MB each)"}}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +114,8 @@ def main():
     ap.add_argument("--backward", default="auto", choices=["auto", "recompute", "stash"],
                     help="backward mode of the library; auto = single-pass (stash) with max_seq_len = the config's longest response")
     ap.add_argument("--len-div", type=int, default=1, help="shorten every sequence (debug / profiling runs)")
+    ap.add_argument("--path", default="policy-loss", choices=["policy-loss", "logz-head"],
+                    help="logz-head: time the small upstream head (forward + backward) instead of the hot path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (reference dispatch for FETCH_SIZE / WRITE_SIZE)")
@@ -88,6 +131,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if a.path == "logz-head":
+        return bench_logz_head(a, dev)
     b = synth.make_rollouts(a.config, dev, a.layout, len_div=a.len_div)
     cfg = b.cfg
     obj = binding.OBJECTIVES[a.objective]

@@ -195,7 +195,7 @@ int32_t rl_default_chunk_rows(void);
  * states are constants).  All pointers are device pointers.
  *   prompt_hidden [rows, H] in `dtype` (rl_dtype), row-major; prompt p owns rows [cu_prompt[p], cu_prompt[p+1])
  *                 (cu_prompt: P+1 int32; an empty prompt pools to zero; ranges are clamped to [0, rows]);
- *   W1 [M, H] f32 row-major (16-byte aligned), b1 [M], w2 [M], b2 [1] f32; H must be a multiple of 4;
+ *   W1 [M, H] f32 row-major, b1 [M], w2 [M], b2 [1] f32 (M at most 524280);
  *   log_z [P] f32, overwritten.
  * The workspace (rl_logz_head_workspace_bytes, 256-byte aligned, caller-owned) keeps the pooled states and
  * the hidden-layer activations between the two calls: rl_logz_head_backward must be given the workspace of
@@ -211,8 +211,8 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
                                 float* dW1, float* db1, float* dw2, float* db2,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* Benchmark aid: runs a pure bf16 MFMA issue loop (v_mfma_f32_32x32x16_bf16, 16 independent
- * accumulators per wavefront, four wavefronts per CU, no memory traffic) for about `millis` ms on
+/* Benchmark aid: runs a pure bf16 MFMA issue loop (v_mfma_f32_16x16x32_bf16 in the hot kernel's 8 x 8 register
+ * blocking, pseudo-random operands, four wavefronts per CU, no memory traffic) for about `millis` ms on
  * `stream`, SYNCHRONISES on it, and returns the rate it reached and the shader clock it ran at.  This is
  * the ceiling any MFMA-bound kernel can approach on this part at this moment (clock throttling included).
  * scratch: device buffer of at least 1 MiB owned by the caller. */

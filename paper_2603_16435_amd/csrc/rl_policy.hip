@@ -556,17 +556,18 @@ __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int col
 
 // ------------------------------------------------------------------ MFMA ceiling probe (benchmark aid)
 __global__ __launch_bounds__(256) void mfma_peak_kernel(float* out, int iters, long long* clk) {
-  floatx16 acc[16];
+  // the hot kernel's own instruction and register blocking: 8 x 8 blocks of v_mfma_f32_16x16x32_bf16
+  floatx4 acc[64];
 #pragma unroll
-  for (int i = 0; i < 16; ++i)
+  for (int i = 0; i < 64; ++i)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-  // operands: pseudo-random bf16 values in (-1,1), two sets alternated so that the inputs toggle the
-  // way real data does (constant operands let the part hold 2.4 GHz; real ones do not)
-  bf16x8 a[2], b[2];
+    for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
+  // operands: pseudo-random bf16 values in (-1,1) (constant or small-integer operands let the part hold
+  // 2.4 GHz; real data does not: it is the values that cost power)
+  bf16x8 a[8], b[8];
   unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
 #pragma unroll
-  for (int k = 0; k < 2; ++k)
+  for (int k = 0; k < 8; ++k)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       h = h * 1664525u + 1013904223u; a[k][e] = (bf16_t)(((int)(h >> 8) & 0xffff) * (1.f / 32768.f) - 1.f);
@@ -575,14 +576,14 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(float* out, int iters, l
   const long long t0 = clock64(), w0 = wall_clock64();
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 1], b[(i >> 1) & 1], acc[i], 0, 0, 0);
+    for (int i = 0; i < 64; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i >> 3], b[i & 7], acc[i], 0, 0, 0);
   }
   const long long t1 = clock64(), w1 = wall_clock64();
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < 16; ++i)
+  for (int i = 0; i < 64; ++i)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) s += acc[i][e];
+    for (int e = 0; e < 4; ++e) s += acc[i][e];
   out[blockIdx.x * blockDim.x + threadIdx.x] = s;
   if (threadIdx.x == 0) { clk[blockIdx.x * 2] = t1 - t0; clk[blockIdx.x * 2 + 1] = w1 - w0; }
 }
@@ -937,8 +938,8 @@ rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_byt
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* out = static_cast<float*>(scratch);
   long long* clk = reinterpret_cast<long long*>(out + kBlocks * 256);
-  // one launch of `iters` rounds of 16 MFMAs per wavefront: ~32 cycles per MFMA, 4 workgroups share a CU
-  const double cycles_per_round = 16.0 * 32.0 * 4.0;
+  // one launch of `iters` rounds of 64 MFMAs per wavefront: ~16 cycles per MFMA, 4 workgroups share a CU
+  const double cycles_per_round = 64.0 * 16.0 * 4.0;
   int iters = (int)(millis * 1e-3 * 2.0e9 / cycles_per_round);
   if (iters < 16) iters = 16;
   hipEvent_t e0, e1;
@@ -954,7 +955,7 @@ rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_byt
   if (st == RL_OK && hipMemcpy(h, clk, sizeof(h), hipMemcpyDeviceToHost) != hipSuccess) st = RL_ERR_HIP;
   (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
   if (st != RL_OK) return st;
-  *tflops = (double)kBlocks * 4.0 * iters * 16.0 * 32768.0 / (ms * 1e-3) / 1e12;
+  *tflops = (double)kBlocks * 4.0 * iters * 64.0 * 16384.0 / (ms * 1e-3) / 1e12;
   *shader_mhz = h[1] > 0 ? 100.0 * (double)h[0] / (double)h[1] : 0.0;   // wall clock ticks at 100 MHz
   return RL_OK;
 }
@@ -1047,7 +1048,7 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
 
 // ------------------------------------------------------------------ log-Z head
 static rl_status logz_check(int32_t P, int32_t H, int32_t M) {
-  if (P < 1 || H < 1 || M < 1 || P > (1 << 20) || (H % 4) != 0) return RL_ERR_SHAPE;
+  if (P < 1 || H < 1 || M < 1 || P > (1 << 20) || (int64_t)((M + 7) / 8) > 65535) return RL_ERR_SHAPE;
   return RL_OK;
 }
 
@@ -1070,22 +1071,15 @@ rl_status rl_logz_head_forward(const void* prompt_hidden, int32_t dtype, int64_t
   if (rows < 0) return RL_ERR_SHAPE;
   const LogzPlan q = logz_plan(P, H, M);
   if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || ws_bytes < q.total) return RL_ERR_WORKSPACE;
-  if ((reinterpret_cast<uintptr_t>(W1) & 15)) return RL_ERR_SHAPE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   (void)hipGetLastError();
   unsigned char* w = static_cast<unsigned char*>(ws);
   float* pooled = (float*)(w + q.off_pooled); float* a = (float*)(w + q.off_a); float* g = (float*)(w + q.off_g);
-  dim3 gp(P, (H + 255) / 256);
+  dim3 gp(P, (H + 63) / 64);
   if (dtype == RL_BF16) logz_pool_kernel<bf16_t><<<gp, 256, 0, s>>>(static_cast<const bf16_t*>(prompt_hidden), rows, H, cu_prompt, pooled);
   else logz_pool_kernel<float><<<gp, 256, 0, s>>>(static_cast<const float*>(prompt_hidden), rows, H, cu_prompt, pooled);
-  // hidden layer as one NT contraction: A = W1 [M][H], B = pooled [P][H]; prompts in groups of one tile column
-  for (int p0 = 0; p0 < P; p0 += kBN) {
-    const int np = P - p0 < kBN ? P - p0 : kBN;
-    GemmDims d{};
-    d.M = M; d.N = np; d.K = H; d.lda = H; d.ldb = H; d.group_m = 1;
-    EpiMlpHidden e{b1, a + (int64_t)p0 * M, g + (int64_t)p0 * M, M, np};
-    launch_generic<float, EpiMlpHidden>(W1, pooled + (int64_t)p0 * H, d, e, (M + kBM - 1) / kBM, s);
-  }
+  dim3 gh((M + 15) / 16, (P + 15) / 16);
+  logz_hidden_kernel<<<gh, 256, 0, s>>>(W1, b1, pooled, P, H, M, a, g);
   logz_out_kernel<<<P, 256, 0, s>>>(g, w2, b2, M, log_z);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
@@ -1104,7 +1098,7 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
   float* pooled = (float*)(w + q.off_pooled); float* a = (float*)(w + q.off_a); float* g = (float*)(w + q.off_g);
   float* da = (float*)(w + q.off_da);
   logz_bwd_vec_kernel<<<(M + 255) / 256, 256, 0, s>>>(d_log_z, a, g, w2, P, M, da, db1, dw2, db2);
-  dim3 gw((H + 255) / 256, M);
+  dim3 gw((H + 255) / 256, (M + 7) / 8);
   logz_bwd_w1_kernel<<<gw, 256, 0, s>>>(da, pooled, P, M, H, dW1);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }

@@ -121,13 +121,13 @@ def test_logz_head_arguments_are_validated_on_the_host(lib):
     assert lib.rl_logz_head_workspace_bytes(16, 3584, 3584, C.byref(n)) == 0
     assert n.value >= 4 * 16 * (3584 + 3 * 3584) and n.value % 256 == 0
     assert lib.rl_logz_head_workspace_bytes(16, 3584, 3584, None) == 1
-    for bad in ((0, 64, 64), (4, 0, 64), (4, 64, 0), (4, 66, 64)):
+    for bad in ((0, 64, 64), (4, 0, 64), (4, 64, 0), (4, 64, 1 << 20)):
         assert lib.rl_logz_head_workspace_bytes(*bad, C.byref(n)) == 2, bad
     fake = 0x1000
     f = lib.rl_logz_head_forward
     assert f(None, 1, 10, 64, fake, 2, fake, fake, fake, fake, 8, fake, fake, 1 << 30, None) == 1
     assert f(fake, 5, 10, 64, fake, 2, fake, fake, fake, fake, 8, fake, fake, 1 << 30, None) == 3
-    assert f(fake, 1, 10, 66, fake, 2, fake, fake, fake, fake, 8, fake, fake, 1 << 30, None) == 2
+    assert f(fake, 1, -1, 64, fake, 2, fake, fake, fake, fake, 8, fake, fake, 1 << 30, None) == 2
     assert f(fake, 1, 10, 64, fake, 2, fake, fake, fake, fake, 8, fake, None, 0, None) == 5
     assert f(fake, 1, 10, 64, fake, 2, fake, fake, fake, fake, 8, fake, fake, 16, None) == 5
     bw = lib.rl_logz_head_backward

@@ -25,9 +25,9 @@ def _head(seed, P, H, M, lens, dtype):
 
 
 @pytest.mark.parametrize("dtype,P,H,M,lens", [
-    (torch.float32, 5, 36, 50, (4, 1, 0, 7, 3)),                        # ragged everything, an empty prompt, K tail (H % 32 != 0)
+    (torch.float32, 5, 37, 50, (4, 1, 0, 7, 3)),                        # ragged everything (odd H, M % 16 != 0), an empty prompt
     (torch.bfloat16, 16, 3584, 3584, tuple(range(100, 900, 50))),       # the 7B-shaped head: 16 prompts, H = M = 3584
-    (torch.bfloat16, 300, 256, 520, tuple(3 + (i % 11) for i in range(300))),   # more prompts than one tile column (P > 256)
+    (torch.bfloat16, 300, 256, 520, tuple(3 + (i % 11) for i in range(300))),   # many prompts (several groups of 16), ragged M
 ])
 def test_logz_head_matches_the_oracle(dtype, P, H, M, lens):
     X, cu, W1, b1, w2, b2, d = _head(11, P, H, M, lens, dtype)
