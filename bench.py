@@ -102,6 +102,47 @@ def bench_logz_head(a, dev):
     print(json.dumps(out), flush=True)
 
 
+def bench_rvq_encode(a, dev):
+    """Residual-VQ encode of one local window of key-cache vectors in the paper's 8B setting: N = 56 codebooks of
+    S = 1024 entries, D = 128, L = 1024 vectors per (layer, head) group; 64 groups per call here."""
+    import numpy as np
+    import torch
+    from paper_2603_16435_amd import binding, synth
+    G, L, N, S, D = 64, 1024, 56, 1024, 128
+    x, cb = synth.make_rvq_case(G, L, N, S, D, device=dev)
+    norms = binding.rl_rvq_codebook_norms(cb)
+    for _ in range(max(a.warmup, 1)):
+        binding.rl_rvq_encode(x, cb, norms)
+    torch.cuda.synchronize()
+    steps = max(a.steps, 5)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        codes, res = binding.rl_rvq_encode(x, cb, norms)
+    e1.record(); torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / steps
+    flops = 2.0 * G * L * S * D * N
+    out = {"metric": "residual-VQ encode, vectors/s", "value": G * L / sec, "unit": "vectors/s", "n_gpus": 1, "steps": steps,
+           "warmup": max(a.warmup, 1), "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"key-cache window of the paper's 8B setting: G={G} groups x L={L} vectors, D={D}, N={N} stages of S={S} entries "
+                                  "(synthetic Gaussian codebooks; no trained ones exist here)"},
+           "roofline": {"bound": "mfma", "kernel": "rvq_encode_kernel", "achieved": flops / sec / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": flops / sec / 1e12 / PEAK_BF16_TFLOPS, "traffic": None,
+                        "note": "2 L S D N flop per group; with K = D = 128 every MFMA output needs ~4 VALU operations of arg-max bookkeeping, "
+                                "so the kernel is co-limited by the vector ALU"}}
+    if not a.no_cpu_baseline:
+        from oracle import rvq_oracle as rvq
+        xs = x[0, :64].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        cbs = cb[0].cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        t0 = time.perf_counter()
+        rvq.rvq_encode(xs, cbs)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 64 / dt, "unit": "vectors/s", "cores": 1, "kind": "oracle",
+                               "sample": f"64 vectors of group 0, all {N} stages, float64, {dt:.1f} s"}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,7 +155,7 @@ def main():
     ap.add_argument("--backward", default="auto", choices=["auto", "recompute", "stash"],
                     help="backward mode of the library; auto = single-pass (stash) with max_seq_len = the config's longest response")
     ap.add_argument("--len-div", type=int, default=1, help="shorten every sequence (debug / profiling runs)")
-    ap.add_argument("--path", default="policy-loss", choices=["policy-loss", "logz-head"],
+    ap.add_argument("--path", default="policy-loss", choices=["policy-loss", "logz-head", "rvq-encode"],
                     help="logz-head: time the small upstream head (forward + backward) instead of the hot path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -133,6 +174,8 @@ def main():
     torch.cuda.set_device(dev)
     if a.path == "logz-head":
         return bench_logz_head(a, dev)
+    if a.path == "rvq-encode":
+        return bench_rvq_encode(a, dev)
     b = synth.make_rollouts(a.config, dev, a.layout, len_div=a.len_div)
     cfg = b.cfg
     obj = binding.OBJECTIVES[a.objective]

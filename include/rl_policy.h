@@ -211,6 +211,22 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
                                 float* dW1, float* db1, float* dw2, float* db2,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/* Residual vector-quantisation encode of KV-cache vectors: the compression step of the paper (method section,
+ * "Learning High-fidelity VQ Codebooks", Eq. 1-2, and the prefill stage, Eq. 5-8).  For each of G independent
+ * codebook groups (one per layer / head / cache type) and each of its L vectors x (D = 128 values, bf16):
+ *     for i = 0..N-1:   codes[i] = argmin_s || r - c[i][s] ||^2  (lowest index on ties),   r <- bf16(r - c[i][codes[i]]),
+ * starting from r = x, where c[i][s] are the effective entries of codebook i (the paper's W_i q_s, stored already
+ * projected) and the running residual is kept in the 16-bit storage precision between stages.
+ *   vectors   [G][L][D] bf16, 16-byte aligned;       codebooks [G][N][S][D] bf16, 16-byte aligned;
+ *   norms     [G][N][S] f32: squared norms of the entries, as written by rl_rvq_codebook_norms (once per codebook set);
+ *   codes     [G][L][N] int32, overwritten (each in [0, S));
+ *   residual  [G][L][D] bf16 or NULL: what is left of each vector after the N stages.
+ * D must be 128 and S a multiple of 64 (else RL_ERR_SHAPE).  All pointers are device pointers; the calls allocate
+ * nothing, do not synchronise, and enqueue on `stream`. */
+rl_status rl_rvq_codebook_norms(const void* codebooks, int32_t G, int32_t N, int32_t S, int32_t D, float* norms, void* stream);
+rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,
+                        int32_t N, int32_t S, int32_t* codes, void* residual, void* stream);
+
 /* Benchmark aid: runs a pure bf16 MFMA issue loop (v_mfma_f32_16x16x32_bf16 in the hot kernel's 8 x 8 register
  * blocking, pseudo-random operands, four wavefronts per CU, no memory traffic) for about `millis` ms on
  * `stream`, SYNCHRONISES on it, and returns the rate it reached and the shader clock it ran at.  This is

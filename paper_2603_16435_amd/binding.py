@@ -99,6 +99,11 @@ def lib() -> C.CDLL:
         L.rl_logz_head_backward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.rl_logz_head_backward.restype = C.c_int
+        L.rl_rvq_codebook_norms.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.rl_rvq_codebook_norms.restype = C.c_int
+        L.rl_rvq_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p]
+        L.rl_rvq_encode.restype = C.c_int
         L.rl_version.restype = C.c_int32
         L.rl_default_chunk_rows.restype = C.c_int32
         _lib = L
@@ -325,4 +330,28 @@ def rl_logz_head_backward(d_log_z, w2, H, workspace):
     _check(lib().rl_logz_head_backward(d_log_z.data_ptr(), P, H, M, w2.data_ptr(), dW1.data_ptr(), db1.data_ptr(), dw2.data_ptr(),
                                        db2.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream_handle()))
     return dW1, db1, dw2, db2
+
+
+# ------------------------------------------------------------------ residual-VQ encode
+def rl_rvq_codebook_norms(codebooks):
+    """Squared norms [G, N, S] (float32) of the codebook entries [G, N, S, D] (bfloat16): computed once per codebook set."""
+    G, N, S, D = codebooks.shape
+    assert codebooks.dtype == torch.bfloat16 and codebooks.is_contiguous()
+    norms = torch.empty(G, N, S, dtype=torch.float32, device=codebooks.device)
+    _check(lib().rl_rvq_codebook_norms(codebooks.data_ptr(), G, N, S, D, norms.data_ptr(), _stream_handle()))
+    return norms
+
+
+def rl_rvq_encode(vectors, codebooks, norms=None, want_residual=True):
+    """codes [G, L, N] int32 (and the residual [G, L, D] bfloat16) of vectors [G, L, D] under codebooks [G, N, S, D]."""
+    G, L, D = vectors.shape
+    _, N, S, _ = codebooks.shape
+    assert vectors.dtype == torch.bfloat16 and vectors.is_contiguous() and codebooks.shape[0] == G and codebooks.shape[3] == D
+    if norms is None:
+        norms = rl_rvq_codebook_norms(codebooks)
+    codes = torch.empty(G, L, N, dtype=torch.int32, device=vectors.device)
+    res = torch.empty_like(vectors) if want_residual else None
+    _check(lib().rl_rvq_encode(vectors.data_ptr(), codebooks.data_ptr(), norms.data_ptr(), G, L, D, N, S, codes.data_ptr(),
+                               res.data_ptr() if want_residual else None, _stream_handle()))
+    return codes, res
 

@@ -22,6 +22,7 @@
 #include "../../include/rl_policy.h"
 #include "epilogues.h"
 #include "logz_head.h"
+#include "rvq_encode.h"
 #include "gemm_nt.h"
 
 namespace rlk {
@@ -926,7 +927,7 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 104; }
+int32_t rl_version(void) { return 105; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
 
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
@@ -1100,6 +1101,37 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
   logz_bwd_vec_kernel<<<(M + 255) / 256, 256, 0, s>>>(d_log_z, a, g, w2, P, M, da, db1, dw2, db2);
   dim3 gw((H + 255) / 256, (M + 7) / 8);
   logz_bwd_w1_kernel<<<gw, 256, 0, s>>>(da, pooled, P, M, H, dW1);
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+// ------------------------------------------------------------------ residual-VQ encode
+static rl_status rvq_check(int32_t G, int64_t L, int32_t D, int32_t N, int32_t S) {
+  if (G < 1 || G > 65535 || L < 1 || L > ((int64_t)1 << 24) || N < 1 || S < 1) return RL_ERR_SHAPE;
+  if (D != kRvqD || (S % kRvqChunk) != 0 || (int64_t)N * S > ((int64_t)1 << 26)) return RL_ERR_SHAPE;
+  return RL_OK;
+}
+
+rl_status rl_rvq_codebook_norms(const void* codebooks, int32_t G, int32_t N, int32_t S, int32_t D, float* norms, void* stream) {
+  if (!codebooks || !norms) return RL_ERR_NULL;
+  rl_status st = rvq_check(G, 1, D, N, S);
+  if (st != RL_OK) return st;
+  if (reinterpret_cast<uintptr_t>(codebooks) & 15) return RL_ERR_SHAPE;
+  (void)hipGetLastError();
+  const int64_t entries = (int64_t)G * N * S;
+  rvq_norms_kernel<<<(unsigned)((entries + 255) / 256), 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const bf16_t*>(codebooks), entries, norms);
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,
+                        int32_t N, int32_t S, int32_t* codes, void* residual, void* stream) {
+  if (!vectors || !codebooks || !norms || !codes) return RL_ERR_NULL;
+  rl_status st = rvq_check(G, L, D, N, S);
+  if (st != RL_OK) return st;
+  if ((reinterpret_cast<uintptr_t>(vectors) | reinterpret_cast<uintptr_t>(codebooks) | reinterpret_cast<uintptr_t>(residual)) & 15) return RL_ERR_SHAPE;
+  (void)hipGetLastError();
+  dim3 grid((unsigned)((L + kRvqVecs - 1) / kRvqVecs), G);
+  rvq_encode_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const bf16_t*>(vectors), static_cast<const bf16_t*>(codebooks), norms,
+                                                                       (int)L, N, S, codes, static_cast<bf16_t*>(residual));
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 

@@ -243,3 +243,21 @@ def make_rollouts(cfg: RolloutConfig | str, device="cpu", layout: str = "padded"
         old_logprob=old, ref_logprob=ref, log_z=log_z.to(dev),
         lengths=ln.to(torch.int32),
     )
+
+
+# --------------------------------------------------------------------------- residual-VQ encode inputs
+_T_RVQ_X, _T_RVQ_CB = 21, 22
+
+
+def make_rvq_case(G: int, L: int, N: int, S: int, D: int = 128, seed: int = 0x5EED0100, device="cpu",
+                  sigma0: float = 0.33, decay: float = 0.945):
+    """Seeded stand-in for a KV-cache segment and its residual codebooks (no trained codebooks exist here):
+    vectors ~ N(0,1) [G, L, D] and codebook stage i ~ N(0, (sigma0 decay^i)^2) [G, N, S, D], both rounded to bf16 once.
+    The stage scales follow the shrinking residual of a greedy search over S random entries (about 10 % of the
+    squared norm per stage at S = 1024, D = 128), so every stage has work to do."""
+    x = normal(seed, _T_RVQ_X, 0, G * L * D, device).view(G, L, D).to(torch.bfloat16)
+    scale = sigma0 * decay ** torch.arange(N, dtype=torch.float32, device=device)
+    cb = normal(seed, _T_RVQ_CB, 0, G * N * S * D, device).view(G, N, S, D)
+    cb = (cb * scale.view(1, N, 1, 1)).to(torch.bfloat16)
+    return x, cb
+
