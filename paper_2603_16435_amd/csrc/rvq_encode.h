@@ -54,7 +54,7 @@ __device__ inline u32x4_t rvq_sub_bf16(const u32x4_t& r, const u32x4_t& c) {   /
 
 // grid (ceil(L / 256), G).  x [G][L][128], cb [G][N][S][128] bf16, cn [G][N][S] f32, codes [G][L][N] int32,
 // residual [G][L][128] bf16 or null.  S % 64 == 0.
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256, 2)
 void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cb, const float* __restrict__ cn,
                        int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual) {
   __shared__ __attribute__((aligned(256))) unsigned char buf[2][kRvqChunk * 256];
@@ -112,13 +112,16 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
     }
     if (t + 1 < total) fetch(t + 1);
     const unsigned char* cur = buf[t & 1];
+    // the accumulators start at -|c|^2/2 of their column, so the MFMAs leave the score r.c - |c|^2/2 directly
     floatx4 acc[4][4];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int c = 0; c < 4; ++c) {
+      const float h = -0.5f * cnc[c];
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
+      for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[rb][c][e] = 0.f;
+        for (int e = 0; e < 4; ++e) acc[rb][c][e] = h;
+    }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       u32x4_t fb[4];
@@ -133,13 +136,12 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
     // scores r.c - |c|^2/2 of rows 16 rb + 4 (l/16) + e against entries ch*64 + 16 c + l%16; candidates come in increasing index
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const float half_norm = 0.5f * cnc[c];
       const int idx = ch * kRvqChunk + c * 16 + e16;
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float v = acc[rb][c][e] - half_norm;
+          const float v = acc[rb][c][e];
           if (v > best[rb][e]) { best[rb][e] = v; bidx[rb][e] = idx; }
         }
     }
