@@ -213,8 +213,8 @@ def main():
         del src, dst
 
     # launches per step that have rows to work on (the library launches a fixed upper bound of chunks; the rest return at once)
-    tc = a.chunk_rows or binding.lib().rl_default_chunk_rows()
     stash = prof["gemm_bwd"][1] > 0
+    tc = a.chunk_rows or (49152 if stash else binding.lib().rl_default_chunk_rows())
     if stash:                                  # sequence-aligned chunks: greedy packing of whole sequences
         real_chunks, rows = 1, 0
         for n in b.lengths.tolist():
@@ -249,14 +249,14 @@ def main():
                                f"{cfg.dtype}, {a.layout} rows R={b.R}, real tokens T={T}, objective={a.objective}"
                                + (f", len_div={a.len_div}" if a.len_div != 1 else ""),
                    "objective": a.objective, "layout": a.layout, "T": T, "R": b.R, "H": cfg.H, "V": cfg.V,
-                   "chunk_rows": a.chunk_rows or binding.lib().rl_default_chunk_rows(), "backward": a.backward},
+                   "chunk_rows": tc, "backward": a.backward},
         "mfma_frac_6THV": 6.0 * thv / (dt / a.steps) / 1e12 / peak,
         "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
         "roofline": {"bound": "mfma", "kernel": f"gemm_nt_bf16_kernel ({dom})", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": (MEASURED_TRAFFIC_7B_CHUNK32768["stash" if stash else "recompute"].get(dom)
                                  if (a.config == "7b" and a.len_div == 1 and a.layout == "padded"
-                                     and (a.chunk_rows or 32768) == 32768) else None),
+                                     and tc == (49152 if stash else 32768)) else None),
                      "traffic_note": "HBM-side bytes of the largest launch of this class (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
                      "launches_with_work": real_chunks * a.steps, "launches": int(dom_n),
                      "avg_launch_ms": dom_ms / max(real_chunks * a.steps, 1),

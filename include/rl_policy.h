@@ -101,7 +101,7 @@ typedef struct rl_params {
   float   beta;                 /* FLOW only: reward scale                               */
   float   adv_eps;              /* added to the group std                                */
   int32_t adv_std_ddof;         /* 0 (population std) or 1                               */
-  int32_t chunk_rows;           /* rows of dS staged at once; 0 = library default.       */
+  int32_t chunk_rows;           /* rows staged at once; 0 = library default (32768; 49152 in single-pass mode) */
                                 /* rounded up to a multiple of 256; sizes the workspace  */
   float   clip_eps_high;        /* upper bound of the ratio / weight is 1 + clip_eps_high; 0 = clip_eps (symmetric) */
   int32_t aggregation;          /* GRPO: RL_AGG_SEQUENCE (mean over sequences of the token mean) or         */
@@ -185,7 +185,7 @@ typedef struct rl_profile {     /* host struct */
 void rl_profile_enable(int32_t on);
 rl_status rl_profile_read(rl_profile* out);
 
-/* Library version (major*100 + minor) and the chunk size used when chunk_rows = 0. */
+/* Library version (major*100 + minor) and the chunk size used when chunk_rows = 0 in recompute mode. */
 int32_t rl_version(void);
 int32_t rl_default_chunk_rows(void);
 
