@@ -164,40 +164,53 @@ struct EpiFwdStash {
   T* ET; int64_t ld_et;   // [Vp][chunk rows = ld_et], slab-tiled
   int V;
 
-  // exponentials, sums and the two stores for block rows 2k, 2k+1 (k = 0..3), eight token columns each
+  // Exponentials, sums and the two stores, in two rounds of four block rows (64 vocabulary entries = one 128-byte
+  // line of a token's E row).  A lane holds 16 bytes of the first half of that line (block rows 4j, 4j+1) and 16 of
+  // the second (4j+2, 4j+3), and its four lane groups make each half 64 bytes wide; lane pairs (token columns cc,
+  // cc^1) swap one half each, so that one store instruction writes whole lines: the eight lanes of the even token's
+  // line first, then the odd token's.
   template <class L, int MB, int NB, bool AGPR, bool PAD>
   __device__ __attribute__((always_inline)) void body(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, int g, int cc, int vleft,
                                                       const float (&rl)[NB], float (&sm)[NB], float (&su)[NB]) const {
+    const int p = cc & 1;
 #pragma unroll
-    for (int k = 0; k < MB / 2; ++k) {
-      const int mrel = k * 32 + g * 8;
-      bf16x2 et[8][NB / 2];                               // [vocab entry i][token pair]: the transposed copy, packed
+    for (int j = 0; j < MB / 4; ++j) {
+      bf16x2 et[16][NB / 2];                              // [vocab entry of the round][token pair]: the transposed copy, packed
 #pragma unroll
       for (int bj = 0; bj < NB; ++bj) {
-        float ev[8];
+        bf16x8 half[2];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float z = acc_read<AGPR>(acc[2 * k + (i >> 2)][bj], i & 3);
-          float v = __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.4426950408889634f, -rl[bj]));
-          if (PAD && !(mrel + i < vleft)) v = 0.f;
-          sm[bj] += v;
-          su[bj] = __builtin_fmaf(v, z, su[bj]);
-          ev[i] = v;
-          et[i][bj >> 1][bj & 1] = (bf16_t)v;
+        for (int kk = 0; kk < 2; ++kk) {
+          const int mrel = (2 * j + kk) * 32 + g * 8;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float z = acc_read<AGPR>(acc[2 * (2 * j + kk) + (i >> 2)][bj], i & 3);
+            float v = __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.4426950408889634f, -rl[bj]));
+            if (PAD && !(mrel + i < vleft)) v = 0.f;
+            sm[bj] += v;
+            su[bj] = __builtin_fmaf(v, z, su[bj]);
+            half[kk][i] = (bf16_t)v;
+            et[kk * 8 + i][bj >> 1][bj & 1] = (bf16_t)v;
+          }
         }
-        bf16x8 row;
+        const u32x4_t a = __builtin_bit_cast(u32x4_t, half[0]), b = __builtin_bit_cast(u32x4_t, half[1]);
+        u32x4_t recv;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) row[i] = (bf16_t)ev[i];
-        store_stream(E + tiled_index(c.n0 + perm_col(bj, cc), c.m0 + mrel, ld_e), row);
+        for (int q = 0; q < 4; ++q)                         // swap with the neighbouring lane (quad_perm [1,0,3,2])
+          recv[q] = (unsigned)__builtin_amdgcn_mov_dpp((int)(p ? a[q] : b[q]), 0xB1, 0xF, 0xF, true);
+        const u32x4_t d_even = p ? recv : a, d_odd = p ? b : recv;
+        const int v0 = c.m0 + j * 64 + p * 32 + g * 8;
+        store_stream(E + tiled_index(c.n0 + perm_col(bj, cc & ~1), v0, ld_e), __builtin_bit_cast(bf16x8, d_even));
+        store_stream(E + tiled_index(c.n0 + perm_col(bj, cc | 1), v0, ld_e), __builtin_bit_cast(bf16x8, d_odd));
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
+      for (int r = 0; r < 16; ++r) {
         bf16x8 col;
 #pragma unroll
-        for (int bj = 0; bj < NB; ++bj) col[bj] = et[i][bj >> 1][bj & 1];
-        store_stream(ET + tiled_index(c.m0 + mrel + i, c.n0 + cc * 8, ld_et), col);
+        for (int bj = 0; bj < NB; ++bj) col[bj] = et[r][bj >> 1][bj & 1];
+        store_stream(ET + tiled_index(c.m0 + (2 * j + (r >> 3)) * 32 + g * 8 + (r & 7), c.n0 + cc * 8, ld_et), col);
       }
-      __builtin_amdgcn_sched_barrier(0);                  // keep the four rounds apart: 64 live values each is plenty
+      __builtin_amdgcn_sched_barrier(0);                  // keep the two rounds apart: 128 live values each is plenty
     }
   }
 
