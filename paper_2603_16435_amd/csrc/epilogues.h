@@ -295,34 +295,40 @@ struct EpiDS {
         lse_l2e[bj] = lse[bj] * 1.4426950408889634f;
       }
       const int vleft = V - c.m0;                          // sub-tile rows >= vleft are vocabulary padding
+      const int p = cc & 1;
 #pragma unroll
-      for (int k = 0; k < MB / 2; ++k) {                   // block rows 2k, 2k+1: vocab offsets k*32 + g*8 .. +7
-        const int mrel = k * 32 + g * 8;
-        bf16_t o[NB][8];
+      for (int j = 0; j < MB / 4; ++j) {                   // four block rows = 64 vocabulary entries = one 128-byte line of a dS row
+        bf16_t o[NB][16];
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj)
 #pragma unroll
-          for (int bb = 0; bb < 2; ++bb)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int m = mrel + bb * 4 + e;
-              const float pr = exp_shifted<T>(acc_read<AGPR>(acc[2 * k + bb][bj], e), lse[bj], lse_l2e[bj]);
-              const float ds = ct[bj] * ((m == y[bj] ? 1.f : 0.f) - pr);
-              o[bj][bb * 4 + e] = (bf16_t)(m < vleft ? ds : 0.f);
-            }
+          for (int r = 0; r < 16; ++r) {                   // r: entry of the round, vocab offset j*64 + (r/8)*32 + g*8 + r%8
+            const int m = (2 * j + (r >> 3)) * 32 + g * 8 + (r & 7);
+            const float pr = exp_shifted<T>(acc_read<AGPR>(acc[4 * j + (r >> 2)][bj], r & 3), lse[bj], lse_l2e[bj]);
+            const float ds = ct[bj] * ((m == y[bj] ? 1.f : 0.f) - pr);
+            o[bj][r] = (bf16_t)(m < vleft ? ds : 0.f);
+          }
+        // token-major copy: lane pairs (token columns cc, cc^1) swap one half each, so that a store writes whole lines
 #pragma unroll
         for (int bj = 0; bj < NB; ++bj) {
-          bf16x8 v;
+          bf16x8 h0, h1;
 #pragma unroll
-          for (int i = 0; i < 8; ++i) v[i] = o[bj][i];
-          store_stream(dS + tiled_index(c.n0 + perm_col(bj, cc), c.m0 + mrel, ld_ds), v);
+          for (int i = 0; i < 8; ++i) { h0[i] = o[bj][i]; h1[i] = o[bj][8 + i]; }
+          const u32x4_t a = __builtin_bit_cast(u32x4_t, h0), b = __builtin_bit_cast(u32x4_t, h1);
+          u32x4_t recv;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) recv[q] = (unsigned)__builtin_amdgcn_mov_dpp((int)(p ? a[q] : b[q]), 0xB1, 0xF, 0xF, true);
+          const u32x4_t d_even = p ? recv : a, d_odd = p ? b : recv;
+          const int v0 = c.m0 + j * 64 + p * 32 + g * 8;
+          store_stream(dS + tiled_index(c.n0 + perm_col(bj, cc & ~1), v0, ld_ds), __builtin_bit_cast(bf16x8, d_even));
+          store_stream(dS + tiled_index(c.n0 + perm_col(bj, cc | 1), v0, ld_ds), __builtin_bit_cast(bf16x8, d_odd));
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int r = 0; r < 16; ++r) {
           bf16x8 v;
 #pragma unroll
-          for (int bj = 0; bj < NB; ++bj) v[bj] = o[bj][i];
-          store_stream(dST + tiled_index(c.m0 + mrel + i, c.n0 + cc * 8, ld_dst), v);
+          for (int bj = 0; bj < NB; ++bj) v[bj] = o[bj][r];
+          store_stream(dST + tiled_index(c.m0 + (2 * j + (r >> 3)) * 32 + g * 8 + (r & 7), c.n0 + cc * 8, ld_dst), v);
         }
       }
     } else {
