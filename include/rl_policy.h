@@ -68,9 +68,10 @@ typedef enum rl_dtype { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
  *                    the drift between old and current policy), and dX / dW are contracted from
  *                    that store (three contractions per chunk, the 6 T H V flops the path needs).
  *                    Needs bf16 inputs, H a multiple of 128, 16-byte aligned hidden / weight and
- *                    0 < params->max_seq_len <= chunk rows; otherwise RL_ERR_RANGE.  Assumes
- *                    |old_logprob - current log-prob| stays far below 80 nats (the stored
- *                    probabilities overflow beyond that and the loss comes back non-finite).
+ *                    0 < params->max_seq_len <= chunk rows; otherwise RL_ERR_RANGE.  old_logprob only
+ *                    steers the reference (clamped to [-40, 0]): the stored probabilities stay
+ *                    representable while the current log-prob of the sampled token is above about
+ *                    -120 nats; beyond that the loss comes back non-finite rather than wrong.
  *  RL_BWD_AUTO       RL_BWD_STASH when its conditions hold, else RL_BWD_RECOMPUTE.
  * Either way at most chunk_rows x V values are held at a time, never T x V. */
 typedef enum rl_aggregation { RL_AGG_SEQUENCE = 0, RL_AGG_TOKEN = 1 } rl_aggregation;

@@ -261,7 +261,7 @@ __global__ void chunk_build_kernel(const int32_t* seq_len, const int32_t* cstart
 
 // One wavefront per compacted row t: target logit zy_t = x_t . W[y_t] (f32 accumulation of bf16 products)
 // and the reference of the stored probabilities, ref_t = zy_t - old_t, which is the logsumexp of the
-// row up to the (small) drift between the old and the current policy.
+// row up to the (small) drift between the old and the current policy (NaN-free for any finite old_t).
 __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, const int32_t* row_map, const int32_t* ids_c,
                                     const float* old_lp, const Ctrl* ctrl, float* zy, float* ref_l2e) {
   const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -281,7 +281,12 @@ __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, con
     }
   }
   for (int o = 32; o > 0; o >>= 1) acc += __shfl_down(acc, o);
-  if (lane == 0) { zy[t] = acc; ref_l2e[t] = (acc - old_lp[r]) * 1.4426950408889634f; }
+  if (lane == 0) {
+    // the old log-prob only steers the reference; clamped to [-40, 0] a wild value costs range, not correctness:
+    // exp(z - ref) stays representable for current log-probs between about -120 and 0
+    const float o = fminf(fmaxf(old_lp[r], -40.f), 0.f);
+    zy[t] = acc; ref_l2e[t] = (acc - o) * 1.4426950408889634f;
+  }
 }
 
 // Per-tile-row partial sums (s, u) of a chunk -> lse, logp, entropy and Z_t = sum_v exp(z - ref_t).

@@ -222,6 +222,19 @@ def test_objective_variants_bf16_both_backward_modes(mode):
             _say("  variant", objective, mode, o_opts, err)
 
 
+def test_stash_mode_with_wild_old_logprobs():
+    # the single-pass backward takes its reference from the old log-probs: values far from the current policy
+    # (here -70 .. +5 nats) must cost range only, never correctness
+    b = _edge_batch("bf16", 128, 1000, [30, 64, 17, 50], P=2, G=2, layout="packed")
+    g = torch.Generator().manual_seed(9)
+    b.old_logprob = (b.old_logprob.cpu() + torch.empty(b.R).uniform_(-60.0, 10.0, generator=g)).cuda()
+    for objective in ("grpo", "flow"):
+        ref = run_oracle(b, objective)
+        res = run_gpu(b, objective, mode="stash")
+        assert np.isfinite(float(res.loss.item()))
+        compare_all(b, res, ref, **BF16_TOL)
+
+
 def test_out_of_range_token_ids_are_masked_and_counted():
     b = _edge_batch("bf16", 64, 512, [6, 4, 7, 3], P=2, G=2, layout="packed")
     bad_rows = [1, 9, 19]
