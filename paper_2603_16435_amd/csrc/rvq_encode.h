@@ -122,16 +122,21 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
 #pragma unroll
         for (int e = 0; e < 4; ++e) acc[rb][c][e] = h;
     }
+    // codebook fragments are read one k-step ahead of the MFMAs that use them
+    u32x4_t fb[2][4];
+    auto frag = [&](int set, int ks) __attribute__((always_inline)) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) fb[set][c] = *reinterpret_cast<const u32x4_t*>(cur + (c * 16 + e16) * 256 + (((ks * 4 + kq) ^ e16) << 4));
+    };
+    frag(0, 0);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      u32x4_t fb[4];
-#pragma unroll
-      for (int c = 0; c < 4; ++c) fb[c] = *reinterpret_cast<const u32x4_t*>(cur + (c * 16 + e16) * 256 + (((ks * 4 + kq) ^ e16) << 4));
+      if (ks < 3) frag((ks + 1) & 1, ks + 1);
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-          acc[rb][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ra[rb][ks]), __builtin_bit_cast(bf16x8, fb[c]), acc[rb][c], 0, 0, 0);
+          acc[rb][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ra[rb][ks]), __builtin_bit_cast(bf16x8, fb[ks & 1][c]), acc[rb][c], 0, 0, 0);
     }
     // scores r.c - |c|^2/2 of rows 16 rb + 4 (l/16) + e against entries ch*64 + 16 c + l%16; candidates come in increasing index
 #pragma unroll
