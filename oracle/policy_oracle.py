@@ -49,11 +49,11 @@ def widen(a) -> np.ndarray:
 # --------------------------------------------------------------------------
 # log-prob:  z = W x_t,  lse_t = log sum_v exp z_v,  logp_t = z[y_t] - lse_t
 # --------------------------------------------------------------------------
-def token_logprob(hidden, weight, token_ids, mask):
-    """Per-token log-probability of the sampled token under softmax(W x_t).
+def token_logprob(hidden, weight, token_ids, mask, temperature=1.0):
+    """Per-token log-probability of the sampled token under softmax(W x_t / temperature).
 
-    Returns (logp[R], lse[R]); masked rows give 0 in both.  lse is computed with
-    the row maximum subtracted (same value, no overflow)."""
+    Returns (logp[R], lse[R]) of the tempered logits; masked rows give 0 in both.  lse is
+    computed with the row maximum subtracted (same value, no overflow)."""
     X = widen(hidden)
     W = widen(weight)
     ids = np.asarray(token_ids).astype(np.int64)
@@ -67,6 +67,7 @@ def token_logprob(hidden, weight, token_ids, mask):
         if rows.size == 0:
             continue
         Z = X[rows] @ W.T                       # [n, V] logits
+        Z = Z / temperature
         M = Z.max(axis=1)
         l = M + np.log(np.exp(Z - M[:, None]).sum(axis=1))
         zy = Z[np.arange(rows.size), ids[rows]]
@@ -75,9 +76,9 @@ def token_logprob(hidden, weight, token_ids, mask):
     return logp, lse
 
 
-def token_entropy(hidden, weight, mask):
-    """Entropy of the full next-token distribution, H_t = -sum_v p_v log p_v with p = softmax(W x_t)
-    (0 log 0 = 0), written out from the definition.  Masked rows give 0."""
+def token_entropy(hidden, weight, mask, temperature=1.0):
+    """Entropy of the full next-token distribution, H_t = -sum_v p_v log p_v with
+    p = softmax(W x_t / temperature) (0 log 0 = 0), written out from the definition.  Masked rows give 0."""
     X = widen(hidden)
     W = widen(weight)
     m = np.asarray(mask).astype(bool)
@@ -88,7 +89,7 @@ def token_entropy(hidden, weight, mask):
         rows = np.nonzero(m[s:e])[0] + s
         if rows.size == 0:
             continue
-        Z = X[rows] @ W.T
+        Z = X[rows] @ W.T / temperature
         Z = Z - Z.max(axis=1, keepdims=True)
         P = np.exp(Z)
         P /= P.sum(axis=1, keepdims=True)
@@ -316,8 +317,9 @@ def flow_loss_variant(logp, old_logprob, ref_logprob, mask, cu_seqlens, adv, gro
 # --------------------------------------------------------------------------
 # backward through log-softmax and the LM head
 # --------------------------------------------------------------------------
-def lm_head_backward(hidden, weight, token_ids, mask, lse, c, want_dw=True):
-    """Given c_t = dloss/dlogp_t:  dS[t,v] = c_t (1[v = y_t] - p[t,v]),  p = exp(z - lse_t),
+def lm_head_backward(hidden, weight, token_ids, mask, lse, c, want_dw=True, temperature=1.0):
+    """Given c_t = dloss/dlogp_t:  dS[t,v] = c_t (1[v = y_t] - p[t,v]) / temperature,
+    p = exp(z - lse_t) with z = W x_t / temperature (dS is the gradient with respect to W x_t),
     dX = dS W,  dW = dS^T X.  Masked rows: dX row = 0, no contribution to dW."""
     X = widen(hidden); W = widen(weight)
     ids = np.asarray(token_ids).astype(np.int64)
@@ -331,9 +333,9 @@ def lm_head_backward(hidden, weight, token_ids, mask, lse, c, want_dw=True):
         if rows.size == 0:
             continue
         Z = X[rows] @ W.T
-        dS = -np.exp(Z - lse[rows][:, None])
+        dS = -np.exp(Z / temperature - lse[rows][:, None])
         dS[np.arange(rows.size), ids[rows]] += 1.0
-        dS *= c[rows][:, None]
+        dS *= c[rows][:, None] / temperature
         dX[rows] = dS @ W
         if want_dw:
             dW += dS.T @ X[rows]
@@ -346,11 +348,12 @@ GRPO, FLOW = 0, 1
 def policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx,
                         rewards, old_logprob, ref_logprob, log_z, P,
                         clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
-                        want_dw=True, want_grads=True, want_entropy=False, variant=None):
+                        want_dw=True, want_grads=True, want_entropy=False, variant=None, temperature=1.0):
     """The whole path in the order of the problem statement: log-prob, per-sequence lengths,
     group-relative advantage, loss + per-token coefficient, backward through the LM head.
-    variant: optional dict of the keyword options of grpo_loss_variant / flow_loss_variant."""
-    logp, lse = token_logprob(hidden, weight, token_ids, mask)
+    variant: optional dict of the keyword options of grpo_loss_variant / flow_loss_variant.
+    temperature: the policy is softmax(W x_t / temperature)."""
+    logp, lse = token_logprob(hidden, weight, token_ids, mask, temperature)
     seq_len = segment_lengths(mask, cu_seqlens)
     adv = group_advantage(rewards, group_idx, P, adv_eps, adv_std_ddof)
     if objective == GRPO and variant:
@@ -369,9 +372,9 @@ def policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, 
         raise ValueError("objective")
     out.update(logprob=logp, lse=lse, seq_len=seq_len, advantages=adv)
     if want_entropy:
-        out["entropy"] = token_entropy(hidden, weight, mask)
+        out["entropy"] = token_entropy(hidden, weight, mask, temperature)
     if want_grads:
-        dX, dW = lm_head_backward(hidden, weight, token_ids, mask, lse, out["c"], want_dw)
+        dX, dW = lm_head_backward(hidden, weight, token_ids, mask, lse, out["c"], want_dw, temperature)
         out["d_hidden"] = dX
         out["d_weight"] = dW
     return out

@@ -32,7 +32,7 @@ MUTANTS = [
     ("flow: unclipped weight", "w[i] = np.exp(min(max(log_ratio, lo_b), hi_b))", "w[i] = np.exp(min(log_ratio, 50.0))"),
     ("flow: gradient factor 2 dropped", "c[rows] = 2.0 * w[i] * delta[i] / (B * n)", "c[rows] = w[i] * delta[i] / (B * n)"),
     ("flow: d_logZ to the wrong prompt", "dz[g[i]] += 2.0 * w[i] * delta[i] / B", "dz[(g[i] + 1) % dz.size] += 2.0 * w[i] * delta[i] / B"),
-    ("backward: softmax minus onehot sign", "dS = -np.exp(Z - lse[rows][:, None])\n        dS[np.arange(rows.size), ids[rows]] += 1.0", "dS = np.exp(Z - lse[rows][:, None])\n        dS[np.arange(rows.size), ids[rows]] -= 1.0"),
+    ("backward: softmax minus onehot sign", "dS = -np.exp(Z / temperature - lse[rows][:, None])\n        dS[np.arange(rows.size), ids[rows]] += 1.0", "dS = np.exp(Z / temperature - lse[rows][:, None])\n        dS[np.arange(rows.size), ids[rows]] -= 1.0"),
     ("backward: dX with transposed weight use", "dX[rows] = dS @ W", "dX[rows] = (dS * 0 + dS.mean(1, keepdims=True)) @ W"),
     ("backward: dW without the transpose", "dW += dS.T @ X[rows]", "dW += (X[rows].T @ dS).T * 0 + dS.T @ np.roll(X[rows], 1, axis=1)"),
     ("backward: masked rows leak", "rows = np.nonzero(m[s:e])[0] + s\n        if rows.size == 0:\n            continue\n        Z = X[rows] @ W.T\n        dS", "rows = np.arange(s, e)\n        if rows.size == 0:\n            continue\n        Z = X[rows] @ W.T\n        dS"),
@@ -44,6 +44,10 @@ MUTANTS = [
     ("variant: sequence ratio gradient ignores clipping", "ds = 0.0 if (hi or lo) else -A * s / n", "ds = -A * s / n"),
     ("variant: sequence ratio KL not averaged", "seq_loss[i] = -surr + kl_coef * k3.sum() / n", "seq_loss[i] = -surr + kl_coef * k3.sum()"),
     ("variant: flow mean weight not divided", "            log_ratio = log_ratio / n", "            log_ratio = log_ratio * 1.0"),
+    ("temperature multiplies the logits", "        Z = Z / temperature\n", "        Z = Z * temperature\n"),
+    ("temperature: entropy of the untempered distribution", "Z = X[rows] @ W.T / temperature\n", "Z = X[rows] @ W.T\n"),
+    ("temperature: backward probabilities untempered", "dS = -np.exp(Z / temperature - lse[rows][:, None])", "dS = -np.exp(Z - lse[rows][:, None])"),
+    ("temperature: chain factor dropped in the backward", "dS *= c[rows][:, None] / temperature", "dS *= c[rows][:, None]"),
     ("variant: flow upper bound", "hi_b = np.log(1.0 + (clip_eps if clip_eps_high is None else clip_eps_high))", "hi_b = np.log(1.0 + clip_eps)"),
 ]
 

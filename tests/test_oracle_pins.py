@@ -536,3 +536,89 @@ def test_flow_variant_gradient_with_frozen_weight():
             num = (o["w"] * (dp ** 2 - dm ** 2)).sum() / B / (2 * h)          # w held at the base point
             assert o["c"][t] == pytest.approx(num, rel=2e-7, abs=1e-9)
 
+
+
+# ---------------------------------------------------------------------------
+# temperature: the policy is softmax(W x / tau)
+# ---------------------------------------------------------------------------
+def test_temperature_logprob_entropy_against_library_and_closed_forms():
+    rng = np.random.default_rng(31)
+    X, W, ids = _rand_problem(rng, R=9, H=5, V=8)
+    mask = np.ones(9, np.uint8)
+    for tau in (0.5, 1.0, 1.7):
+        lp, lse = orc.token_logprob(X, W, ids, mask, temperature=tau)
+        ref = scipy.special.log_softmax((X @ W.T) / tau, axis=1)
+        np.testing.assert_allclose(lp, ref[np.arange(9), ids], atol=1e-13)
+        np.testing.assert_allclose(lse, scipy.special.logsumexp((X @ W.T) / tau, axis=1), atol=1e-13)
+        ent = orc.token_entropy(X, W, mask, temperature=tau)
+        p = np.exp(ref)
+        np.testing.assert_allclose(ent, -(p * ref).sum(1), atol=1e-13)
+    # the temperature only rescales the head: (W, tau) and (W / tau, 1) are the same policy
+    a, _ = orc.token_logprob(X, W, ids, mask, temperature=0.8)
+    b, _ = orc.token_logprob(X, W / 0.8, ids, mask)
+    np.testing.assert_allclose(a, b, atol=1e-13)
+    # worked example: x = [ln 2, ln 3], W = I2 + zero row, tau = 1/2 squares the odds: p ~ [4, 9, 1] / 14
+    Ww, Xw, idw, mw, _, _ = _worked()
+    lp, lse = orc.token_logprob(Xw[:1], Ww, idw[:1], mw[:1], temperature=0.5)
+    assert lp[0] == pytest.approx(math.log(4 / 14), abs=1e-14) and lse[0] == pytest.approx(math.log(14.0), abs=1e-14)
+    # a hot distribution tends to the uniform one
+    lp, _ = orc.token_logprob(X, W, ids, mask, temperature=1e9)
+    np.testing.assert_allclose(lp, -math.log(8), atol=1e-7)
+    ent = orc.token_entropy(X, W, mask, temperature=1e9)
+    np.testing.assert_allclose(ent, math.log(8), atol=1e-7)
+
+
+def test_temperature_backward_is_the_autograd_gradient_of_tempered_cross_entropy():
+    rng = np.random.default_rng(32)
+    X, W, ids = _rand_problem(rng, R=12, H=6, V=9)
+    mask = np.ones(12, np.uint8)
+    tau = 0.6
+    c = rng.normal(size=12)
+    _, lse = orc.token_logprob(X, W, ids, mask, temperature=tau)
+    dX, dW = orc.lm_head_backward(X, W, ids, mask, lse, c, temperature=tau)
+    Xt = torch.tensor(X, requires_grad=True); Wt = torch.tensor(W, requires_grad=True)
+    lsm = torch.log_softmax(Xt @ Wt.T / tau, dim=1)
+    (torch.tensor(c) * lsm[torch.arange(12), torch.from_numpy(ids)]).sum().backward()
+    np.testing.assert_allclose(dX, Xt.grad.numpy(), atol=1e-13)
+    np.testing.assert_allclose(dW, Wt.grad.numpy(), atol=1e-13)
+    np.testing.assert_allclose(dW.sum(0), 0.0, atol=1e-13)
+
+
+@pytest.mark.parametrize("objective", [orc.GRPO, orc.FLOW])
+def test_temperature_whole_path_by_finite_differences(objective):
+    tau = 0.7
+    pb = _fd_problem(41 + objective)
+    rng = np.random.default_rng(43)
+    lp, _ = orc.token_logprob(pb["hidden"], pb["weight"], pb["token_ids"], pb["mask"], temperature=tau)
+    old = lp + rng.choice([-0.1, 0.05, 0.12], size=lp.size)
+    old[0] = lp[0] - 0.5; old[3] = lp[3] + 0.5
+    pb["old_logprob"] = old
+    pb["ref_logprob"] = lp + rng.normal(size=lp.size) * 0.2
+    base = orc.policy_loss_fwd_bwd(objective, temperature=tau, **pb)
+    np.testing.assert_allclose(base["logprob"], lp, atol=0)
+    w0 = base.get("w")
+
+    def loss_of(**over):
+        q = dict(pb); q.update(over)
+        o = orc.policy_loss_fwd_bwd(objective, want_grads=False, temperature=tau, **q)
+        if objective == orc.FLOW:
+            return float((w0 * o["delta"] ** 2).sum() / w0.size)
+        return float(o["loss"])
+
+    h = 1e-6
+    for name, grad in (("hidden", base["d_hidden"]), ("weight", base["d_weight"])):
+        A = pb[name]
+        fd = np.zeros_like(A)
+        for idx in np.ndindex(*A.shape):
+            Ap = A.copy(); Ap[idx] += h
+            Am = A.copy(); Am[idx] -= h
+            fd[idx] = (loss_of(**{name: Ap}) - loss_of(**{name: Am})) / (2 * h)
+        scale = np.abs(grad).max()
+        assert scale > 1e-3
+        np.testing.assert_allclose(grad, fd, atol=2e-7 * max(scale, 1.0))
+    # same policy written with the temperature folded into the head: dX equal, dW scaled by the chain rule
+    q = dict(pb); q["weight"] = pb["weight"] / tau
+    fold = orc.policy_loss_fwd_bwd(objective, **q)
+    assert fold["loss"] == pytest.approx(base["loss"], abs=1e-13)
+    np.testing.assert_allclose(fold["d_hidden"], base["d_hidden"], atol=1e-13)
+    np.testing.assert_allclose(fold["d_weight"] / tau, base["d_weight"], atol=1e-13)
