@@ -114,6 +114,9 @@ typedef struct rl_params {
   int32_t backward_mode;        /* rl_backward_mode; 0 = RL_BWD_AUTO                     */
   int32_t max_seq_len;          /* promise: no sequence has more counting rows than this; */
                                 /* 0 = no promise.  Needed by the single-pass backward.   */
+  float   temperature;          /* the policy is softmax(W x_t / temperature): logprob, lse, entropy refer to the */
+                                /* tempered logits and d_hidden / d_weight carry the 1/temperature chain factor;  */
+                                /* 0 = 1.0 (logits used as they are); otherwise finite and > 0                    */
 } rl_params;
 
 typedef struct rl_stats {       /* device struct written by the loss call                */
@@ -155,6 +158,11 @@ rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params,
  * cu_seqlens = {0,R}).  Used to score rollouts under the old / reference policies. */
 rl_status rl_token_logprob(const rl_batch* batch, float* logprob, float* lse,
                            void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same under softmax(W x_t / temperature), temperature finite and > 0 (else RL_ERR_RANGE): the
+ * scoring call that matches rl_params.temperature of the loss call.  Same workspace size. */
+rl_status rl_token_logprob_tempered(const rl_batch* batch, float temperature, float* logprob, float* lse,
+                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* The whole path: log-prob, per-sequence length-normalised sums, group advantage, loss and
  * per-token coefficient, and (if d_hidden and d_weight are given) the backward pass. */

@@ -33,7 +33,7 @@ class rl_params(C.Structure):
                 ("adv_std_ddof", C.c_int32), ("chunk_rows", C.c_int32),
                 ("clip_eps_high", C.c_float), ("aggregation", C.c_int32), ("ratio_level", C.c_int32),
                 ("flow_weight_norm", C.c_int32),
-                ("backward_mode", C.c_int32), ("max_seq_len", C.c_int32)]
+                ("backward_mode", C.c_int32), ("max_seq_len", C.c_int32), ("temperature", C.c_float)]
 
 
 class rl_stats(C.Structure):
@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
         L.rl_workspace_bytes.restype = C.c_int
         L.rl_token_logprob.argtypes = [C.POINTER(rl_batch), C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.rl_token_logprob.restype = C.c_int
+        L.rl_token_logprob_tempered.argtypes = [C.POINTER(rl_batch), C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.rl_token_logprob_tempered.restype = C.c_int
         L.rl_policy_loss_fwd_bwd.argtypes = [C.POINTER(rl_batch), C.POINTER(rl_params), C.c_int32,
                                              C.POINTER(rl_outputs), C.c_void_p, C.c_size_t, C.c_void_p]
         L.rl_policy_loss_fwd_bwd.restype = C.c_int
@@ -181,6 +183,15 @@ def _stream_handle() -> int:
 
 def rl_token_logprob(hidden, weight, token_ids, mask, cu_seqlens=None, workspace=None):
     """Forward only: (logprob[R], lse[R]) float32; masked rows read 0."""
+    return _token_logprob(hidden, weight, token_ids, mask, cu_seqlens, workspace, None)
+
+
+def rl_token_logprob_tempered(hidden, weight, token_ids, mask, temperature, cu_seqlens=None, workspace=None):
+    """The same under softmax(W x / temperature)."""
+    return _token_logprob(hidden, weight, token_ids, mask, cu_seqlens, workspace, float(temperature))
+
+
+def _token_logprob(hidden, weight, token_ids, mask, cu_seqlens, workspace, temperature):
     R = hidden.shape[0]
     dev = hidden.device
     if cu_seqlens is None:
@@ -190,8 +201,12 @@ def rl_token_logprob(hidden, weight, token_ids, mask, cu_seqlens=None, workspace
     ws = workspace if workspace is not None else _workspace(need, dev)
     logp = torch.empty(R, dtype=torch.float32, device=dev)
     lse = torch.empty(R, dtype=torch.float32, device=dev)
-    _check(lib().rl_token_logprob(C.byref(b), logp.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
-                                  _stream_handle()))
+    if temperature is None:
+        _check(lib().rl_token_logprob(C.byref(b), logp.data_ptr(), lse.data_ptr(), ws.data_ptr(), ws.numel(),
+                                      _stream_handle()))
+    else:
+        _check(lib().rl_token_logprob_tempered(C.byref(b), temperature, logp.data_ptr(), lse.data_ptr(), ws.data_ptr(),
+                                               ws.numel(), _stream_handle()))
     return logp, lse
 
 
@@ -259,22 +274,24 @@ def _enum(table, v):
 
 def make_params(clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0, chunk_rows=0,
                 backward_mode="auto", max_seq_len=0, clip_eps_high=0.0, aggregation="sequence",
-                ratio_level="token", flow_weight_norm="sum") -> rl_params:
+                ratio_level="token", flow_weight_norm="sum", temperature=0.0) -> rl_params:
     return rl_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows,
                      float(clip_eps_high or 0.0), _enum(AGGREGATIONS, aggregation), _enum(RATIO_LEVELS, ratio_level),
-                     _enum(WEIGHT_NORMS, flow_weight_norm), _enum(BACKWARD_MODES, backward_mode), int(max_seq_len))
+                     _enum(WEIGHT_NORMS, flow_weight_norm), _enum(BACKWARD_MODES, backward_mode), int(max_seq_len),
+                     float(temperature or 0.0))
 
 
 def rl_policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards,
                            old_logprob, ref_logprob, log_z=None, P: Optional[int] = None,
                            clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
                            chunk_rows=0, backward=True, backward_mode="auto", max_seq_len=0, clip_eps_high=0.0,
-                           aggregation="sequence", ratio_level="token", flow_weight_norm="sum") -> LossResult:
+                           aggregation="sequence", ratio_level="token", flow_weight_norm="sum",
+                           temperature=0.0) -> LossResult:
     """One pass of the whole path.  `objective` is "grpo" | "flow" (or the enum value)."""
     obj = OBJECTIVES[objective] if isinstance(objective, str) else int(objective)
     b = make_batch(hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards, old_logprob, ref_logprob, log_z, P)
     prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, backward_mode, max_seq_len,
-                      clip_eps_high, aggregation, ratio_level, flow_weight_norm)
+                      clip_eps_high, aggregation, ratio_level, flow_weight_norm, temperature)
     plan = PolicyLossPlan(b, prm, hidden.device, hidden.dtype, backward)
     return plan.run(obj)
 

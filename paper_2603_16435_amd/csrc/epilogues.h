@@ -20,16 +20,20 @@ template <class T> __device__ inline float fast_exp(float x);
 template <> __device__ inline float fast_exp<bf16_t>(float x) { return __expf(x); }
 template <> __device__ inline float fast_exp<float>(float x) { return expf(x); }
 
-// exp(z - m) with m*log2(e) precomputed: one fma and one v_exp for bf16 inputs, the accurate libm path for f32
-template <class T> __device__ inline float exp_shifted(float z, float m, float m_l2e);
-template <> __device__ inline float exp_shifted<bf16_t>(float z, float, float m_l2e) {
-  return __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.4426950408889634f, -m_l2e));
+constexpr float kLog2e = 1.4426950408889634f;
+
+// exp(zs z - m) for a raw logit z, the inverse temperature zs and a shift m given in tempered units, with
+// m*log2(e) and zs*log2(e) precomputed: one fma and one v_exp for bf16 inputs, the accurate libm path for f32
+template <class T> __device__ inline float exp_shifted(float z, float m, float m_l2e, float zs, float zs_l2e);
+template <> __device__ inline float exp_shifted<bf16_t>(float z, float, float m_l2e, float, float zs_l2e) {
+  return __builtin_amdgcn_exp2f(__builtin_fmaf(z, zs_l2e, -m_l2e));
 }
-template <> __device__ inline float exp_shifted<float>(float z, float m, float) { return expf(z - m); }
+template <> __device__ inline float exp_shifted<float>(float z, float m, float, float zs, float) { return expf(z * zs - m); }
 
 // ---- forward: per-token partial (max m, s = sum exp(z-m), u = sum exp(z-m) z) over this tile's vocab
 //      range + target gather; z_t[y_t] is written by the single lane that holds vocab row y_t of token t.
 //      u feeds the entropy H_t = lse_t - u/s of the full distribution at no extra pass.
+//      z is the tempered logit zs * (W x_t), zs = 1 / temperature; everything written is in tempered units.
 template <class T>
 struct EpiFwd {
   typedef NoPre Pre;
@@ -41,6 +45,7 @@ struct EpiFwd {
   float4* part;         // [tiles_m(V)][ldp] partial (m, s, u, -) per token
   int ldp;              // = chunk rows
   int V;
+  float zs;             // inverse temperature
 
   // one token column of one lane: the MB * kRegs logits it holds.  PAD: some of the sub-tile's rows are
   // vocabulary padding (only in the last tile row) and must not enter the sums.
@@ -58,19 +63,20 @@ struct EpiFwd {
         z[bi * L::kRegs + i] = v;
         mx = fmaxf(mx, (!PAD || L::row(bi, i, lane) < vleft) ? v : NEG);
       }
-    const float ms = (mx == NEG) ? 0.f : mx;
-    const float ms_l2e = ms * 1.4426950408889634f;
+    const float ms = (mx == NEG) ? 0.f : mx * zs;             // zs > 0: the largest raw logit is the largest tempered one
+    const float ms_l2e = ms * kLog2e, zs_l2e = zs * kLog2e;
     sm = 0.f; su = 0.f;
 #pragma unroll
     for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
       for (int i = 0; i < L::kRegs; ++i) {
         const float v = z[bi * L::kRegs + i];
-        float e = exp_shifted<T>(v, ms, ms_l2e);
+        float e = exp_shifted<T>(v, ms, ms_l2e, zs, zs_l2e);
         if (PAD && !(L::row(bi, i, lane) < vleft)) e = 0.f;
         sm += e;
         su = __builtin_fmaf(e, v, su);
       }
+    mx *= zs; su *= zs;
   }
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
@@ -94,7 +100,7 @@ struct EpiFwd {
             const float v = acc_read<AGPR>(acc[bi][bj], i);
             if (L::row(bi, i, c.lane) == yrel) zy = v;
           }
-        zy_c[d.chunk_start + n] = zy;
+        zy_c[d.chunk_start + n] = zy * zs;
       }
       float mx, sm, su;
       if (pad) column<L, MB, NB, AGPR, true>(acc, bj, c.lane, vleft, mx, sm, su);
@@ -163,6 +169,7 @@ struct EpiFwdStash {
   T* E;  int64_t ld_e;    // [chunk rows][Vp = ld_e], slab-tiled
   T* ET; int64_t ld_et;   // [Vp][chunk rows = ld_et], slab-tiled
   int V;
+  float zs;               // inverse temperature: z = zs * (W x_t) is the logit that ref_t, s and u refer to
 
   // Exponentials, sums and the two stores, in two rounds of four block rows (64 vocabulary entries = one 128-byte
   // line of a token's E row).  A lane holds 16 bytes of the first half of that line (block rows 4j, 4j+1) and 16 of
@@ -173,6 +180,7 @@ struct EpiFwdStash {
   __device__ __attribute__((always_inline)) void body(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, int g, int cc, int vleft,
                                                       const float (&rl)[NB], float (&sm)[NB], float (&su)[NB]) const {
     const int p = cc & 1;
+    const float zs_l2e = zs * kLog2e;
 #pragma unroll
     for (int j = 0; j < MB / 4; ++j) {
       bf16x2 et[16][NB / 2];                              // [vocab entry of the round][token pair]: the transposed copy, packed
@@ -185,7 +193,7 @@ struct EpiFwdStash {
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const float z = acc_read<AGPR>(acc[2 * (2 * j + kk) + (i >> 2)][bj], i & 3);
-            float v = __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.4426950408889634f, -rl[bj]));
+            float v = __builtin_amdgcn_exp2f(__builtin_fmaf(z, zs_l2e, -rl[bj]));
             if (PAD && !(mrel + i < vleft)) v = 0.f;
             sm[bj] += v;
             su[bj] = __builtin_fmaf(v, z, su[bj]);
@@ -229,7 +237,7 @@ struct EpiFwdStash {
     for (int bj = 0; bj < NB; ++bj) {
 #pragma unroll
       for (int off = 16; off < 64; off <<= 1) { sm[bj] += __shfl_xor(sm[bj], off); su[bj] += __shfl_xor(su[bj], off); }
-      if (c.lane < 16) red[c.wm * BN + c.wn * (BN / WAVES_N) + perm_col(bj, cc)] = make_float2(sm[bj], su[bj]);
+      if (c.lane < 16) red[c.wm * BN + c.wn * (BN / WAVES_N) + perm_col(bj, cc)] = make_float2(sm[bj], su[bj] * zs);
     }
     __syncthreads();
     if (c.tid < BN) {
@@ -257,7 +265,8 @@ template <> struct Pack4<float> {
   }
 };
 
-// ---- backward, stage 1: recomputed logits -> dS = c_t (1[v=y_t] - exp(z - lse_t)), formed in
+// ---- backward, stage 1: recomputed logits -> dS = zs c_t (1[v=y_t] - exp(z - lse_t)) (z the tempered
+//      logit, zs = 1 / temperature the chain factor back to W x_t), formed in
 //      f32 (subtraction and scaling before rounding) and stored in the input precision twice:
 //      token-major dS[t][v] (operand of dX = dS W) and vocab-major dST[v][t] (operand of
 //      dW = dS^T X), so that both later contractions have K contiguous.
@@ -277,6 +286,7 @@ struct EpiDS {
   T* dST; int64_t ld_dst;   // [Vp][chunk rows]
   int V;
   bool tiled;               // both copies slab-tiled (always so for bf16: their consumer is the hot kernel)
+  float zs;                 // inverse temperature
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char*, const GemmDims& d, const Pre&) const {
@@ -291,9 +301,10 @@ struct EpiDS {
         const int t = d.chunk_start + n;
         y[bj] = valid ? ids_c[t] - c.m0 : -1;             // relative to the sub-tile; -1 never matches
         lse[bj] = valid ? lse_c[t] : 3.0e38f;             // invalid token: p = exp(z - huge) = 0 and
-        ct[bj] = valid ? c_c[t] : 0.f;                    // c = 0, so every dS entry becomes 0
-        lse_l2e[bj] = lse[bj] * 1.4426950408889634f;
+        ct[bj] = valid ? c_c[t] * zs : 0.f;               // c = 0, so every dS entry becomes 0
+        lse_l2e[bj] = lse[bj] * kLog2e;
       }
+      const float zs_l2e = zs * kLog2e;
       const int vleft = V - c.m0;                          // sub-tile rows >= vleft are vocabulary padding
       const int p = cc & 1;
 #pragma unroll
@@ -304,7 +315,7 @@ struct EpiDS {
 #pragma unroll
           for (int r = 0; r < 16; ++r) {                   // r: entry of the round, vocab offset j*64 + (r/8)*32 + g*8 + r%8
             const int m = (2 * j + (r >> 3)) * 32 + g * 8 + (r & 7);
-            const float pr = exp_shifted<T>(acc_read<AGPR>(acc[4 * j + (r >> 2)][bj], r & 3), lse[bj], lse_l2e[bj]);
+            const float pr = exp_shifted<T>(acc_read<AGPR>(acc[4 * j + (r >> 2)][bj], r & 3), lse[bj], lse_l2e[bj], zs, zs_l2e);
             const float ds = ct[bj] * ((m == y[bj] ? 1.f : 0.f) - pr);
             o[bj][r] = (bf16_t)(m < vleft ? ds : 0.f);
           }
@@ -339,7 +350,7 @@ struct EpiDS {
         const int g = d.chunk_start + n;
         const int y = valid ? ids_c[g] : -1;
         const float lse = valid ? lse_c[g] : 0.f;
-        const float ct = valid ? c_c[g] : 0.f;
+        const float ct = valid ? c_c[g] * zs : 0.f;
 #pragma unroll
         for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
@@ -348,7 +359,7 @@ struct EpiDS {
             float o[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float p = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], q * 4 + e) - lse);
+              const float p = fast_exp<T>(acc_read<AGPR>(acc[bi][bj], q * 4 + e) * zs - lse);
               const float ds = ct * (((m + e) == y ? 1.f : 0.f) - p);
               o[e] = (valid && (m + e) < V) ? ds : 0.f;
             }

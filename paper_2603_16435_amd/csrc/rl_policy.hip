@@ -260,10 +260,10 @@ __global__ void chunk_build_kernel(const int32_t* seq_len, const int32_t* cstart
 }
 
 // One wavefront per compacted row t: target logit zy_t = x_t . W[y_t] (f32 accumulation of bf16 products)
-// and the reference of the stored probabilities, ref_t = zy_t - old_t, which is the logsumexp of the
-// row up to the (small) drift between the old and the current policy (NaN-free for any finite old_t).
+// (times the inverse temperature) and the reference of the stored probabilities, ref_t = zy_t - old_t, which is
+// the logsumexp of the row up to the (small) drift between the old and the current policy (NaN-free for any finite old_t).
 __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, const int32_t* row_map, const int32_t* ids_c,
-                                    const float* old_lp, const Ctrl* ctrl, float* zy, float* ref_l2e) {
+                                    const float* old_lp, const Ctrl* ctrl, float inv_tau, float* zy, float* ref_l2e) {
   const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= ctrl->n_real) return;
   const int lane = threadIdx.x & 63;
@@ -285,6 +285,7 @@ __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, con
     // the old log-prob only steers the reference; clamped to [-40, 0] a wild value costs range, not correctness:
     // exp(z - ref) stays representable for current log-probs between about -120 and 0
     const float o = fminf(fmaxf(old_lp[r], -40.f), 0.f);
+    acc *= inv_tau;
     zy[t] = acc; ref_l2e[t] = (acc - o) * 1.4426950408889634f;
   }
 }
@@ -319,16 +320,18 @@ __global__ void lse_sum_kernel(const float2* part, int ldp, int tiles_v, const f
   }
 }
 
-// After the loss: per row of the chunk the factor -c_t / Z_t of the backward contractions, and the
-// target entry of the stored probabilities replaced by e_y - Z_t (so that -c/Z times the stored row is dS).
+// After the loss: per row of the chunk the factor -c_t / (tau Z_t) of the backward contractions (1 / tau: from the
+// tempered logit back to W x_t), and the target entry of the stored probabilities replaced by e_y - Z_t (so that
+// the factor times the stored row is dS).
 template <class T>
 __global__ void stash_patch_kernel(const ChunkDesc* desc, const int32_t* ids_c, const float* zy_c, const float* ref_l2e,
-                                   const float* zsum_c, const float* c_c, float* row_scale, T* E, int64_t ld_e, T* ET, int64_t ld_et) {
+                                   const float* zsum_c, const float* c_c, float inv_tau, float* row_scale,
+                                   T* E, int64_t ld_e, T* ET, int64_t ld_et) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= desc->rows) return;
   const int g = desc->row_start + n;
   const float Z = zsum_c[g];
-  row_scale[n] = -c_c[g] / Z;
+  row_scale[n] = -c_c[g] * inv_tau / Z;
   const float ey = exp2f(fmaf(zy_c[g], 1.4426950408889634f, -ref_l2e[g]));
   const T v = (T)(ey - Z);
   const int y = ids_c[g];
@@ -603,6 +606,7 @@ struct Plan {
   bool tiled;            // bf16: the work buffers dS/E, dS^T/E^T, W^T, X^T are slab-tiled (hot kernel operands)
   bool stash;            // single-pass backward (forward keeps each chunk's unnormalised probabilities)
   int n_desc, max_len;   // stash: number of chunk records, promised bound on rows per sequence
+  float inv_tau;         // 1 / temperature
   size_t off_ctrl, off_seq_len, off_cstart, off_row_map, off_ids_c, off_cpos, off_zy, off_lse_c, off_logp_c,
       off_c_c, off_adv, off_seq_loss, off_gterm, off_part, off_wt, off_xt, off_ds, off_dst,
       off_desc, off_ref, off_zsum, off_scale, total;
@@ -618,6 +622,11 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   if (b->dtype == RL_F32 && (b->H % 4)) return RL_ERR_SHAPE;
   p.R = b->R; p.H = b->H; p.V = b->V; p.B = b->B; p.P = b->P; p.dtype = b->dtype;
   p.esz = b->dtype == RL_BF16 ? 2 : 4;
+  p.inv_tau = 1.f;
+  if (prm && prm->temperature != 0.f) {
+    if (!(prm->temperature > 0.f) || !(prm->temperature <= 3.0e38f)) return RL_ERR_RANGE;
+    p.inv_tau = 1.f / prm->temperature;
+  }
   if (prm && prm->chunk_rows < 0) return RL_ERR_SHAPE;
   const int mode = prm ? prm->backward_mode : RL_BWD_AUTO;
   if (mode != RL_BWD_AUTO && mode != RL_BWD_RECOMPUTE && mode != RL_BWD_STASH) return RL_ERR_RANGE;
@@ -742,7 +751,7 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     GemmDims d{};
     d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
     d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
-    EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V};
+    EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V, p.inv_tau};
     { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm<TuneLogits>(W, X, d, e, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
     lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
@@ -780,7 +789,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
       d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
-      EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V, p.tiled};
+      EpiDS<T> e{q.ids_c, q.lse_c, q.c_c, dS, p.Vp, dST, p.Tc, p.V, p.tiled, p.inv_tau};
       ProfScope ps(RL_PROF_GEMM_DS, s);
       launch_gemm<TuneLogits>(W, X, d, e, s);
     }
@@ -838,7 +847,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
   {
     ProfScope ps(RL_PROF_PREP, s);
     chunk_build_kernel<<<1, 64, 0, s>>>(q.seq_len, q.cstart, p.B, p.Tc, p.max_len, q.desc, p.n_desc, q.ctrl, out->stats);
-    target_logit_kernel<<<(unsigned)((p.R + 3) / 4), 256, 0, s>>>(X, W, p.H, q.row_map, q.ids_c, b->old_logprob, q.ctrl, q.zy, q.ref);
+    target_logit_kernel<<<(unsigned)((p.R + 3) / 4), 256, 0, s>>>(X, W, p.H, q.row_map, q.ids_c, b->old_logprob, q.ctrl, p.inv_tau, q.zy, q.ref);
   }
   float2* part = reinterpret_cast<float2*>(q.part);
   for (int k = 0; k < p.n_desc; ++k) {
@@ -848,7 +857,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
       d.b_rows = q.row_map; d.chunk = chunk; d.dyn = 2; d.group_m = TuneLogits::kBand;
-      EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, ET, p.Tc, p.V};
+      EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, ET, p.Tc, p.V, p.inv_tau};
       ProfScope ps(RL_PROF_GEMM_FWD, s);
       gemm_nt_bf16_kernel<EpiFwdStash<T>, TuneLogits::kPfd, TuneLogits::kVmg, TuneLogits::kVmo>
           <<<((p.V + kBM - 1) / kBM) * ((p.Tc + kBN - 1) / kBN), 256, 0, s>>>(W, X, d, e);
@@ -863,7 +872,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
                                          b->group_idx, b->log_z, p.B, loss_opts(prm), q.ctrl,
                                          q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats, dk);
-      stash_patch_kernel<T><<<(p.Tc + 255) / 256, 256, 0, s>>>(dk, q.ids_c, q.zy, q.ref, q.zsum, q.c_c, q.scale, E, p.Vp, ET, p.Tc);
+      stash_patch_kernel<T><<<(p.Tc + 255) / 256, 256, 0, s>>>(dk, q.ids_c, q.zy, q.ref, q.zsum, q.c_c, p.inv_tau, q.scale, E, p.Vp, ET, p.Tc);
     }
     {  // X^T chunk scaled by -c/Z, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
@@ -933,7 +942,7 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 105; }
+int32_t rl_version(void) { return 106; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
 
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
@@ -977,12 +986,19 @@ rl_status rl_workspace_bytes(const rl_batch* batch, const rl_params* params, int
 }
 
 rl_status rl_token_logprob(const rl_batch* b, float* logprob, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  return rl_token_logprob_tempered(b, 1.f, logprob, lse, ws, ws_bytes, stream);
+}
+
+rl_status rl_token_logprob_tempered(const rl_batch* b, float temperature, float* logprob, float* lse,
+                                    void* ws, size_t ws_bytes, void* stream) {
   if (!b) return RL_ERR_NULL;
   if (!b->hidden || !b->weight || !b->token_ids || !b->mask || !b->cu_seqlens) return RL_ERR_NULL;
   if (!logprob && !lse) return RL_ERR_NULL;
+  if (!(temperature > 0.f) || !(temperature <= 3.0e38f)) return RL_ERR_RANGE;
   Plan p;
   rl_status st = make_plan(b, nullptr, false, p);
   if (st != RL_OK) return st;
+  p.inv_tau = 1.f / temperature;
   st = check_ws(ws, ws_bytes, p);
   if (st != RL_OK) return st;
   hipStream_t s = static_cast<hipStream_t>(stream);

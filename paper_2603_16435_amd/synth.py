@@ -173,7 +173,7 @@ def sequence_lengths(cfg: RolloutConfig, len_div: int = 1) -> torch.Tensor:
 
 def make_rollouts(cfg: RolloutConfig | str, device="cpu", layout: str = "padded",
                   len_div: int = 1, noise: float = 0.05, weight_std: float = 0.02,
-                  lengths=None) -> RolloutBatch:
+                  lengths=None, temperature: float = 1.0) -> RolloutBatch:
     """Build one batch.
 
     layout "padded": R = B*Lmax rows, sequence i owns rows [i*Lmax, (i+1)*Lmax), its first
@@ -182,6 +182,7 @@ def make_rollouts(cfg: RolloutConfig | str, device="cpu", layout: str = "padded"
     len_div > 1 shortens every sequence to ceil(len/len_div) tokens (the token-sub-sampled
     instance of a big configuration: same H, V, P, G, same distributions).
     `lengths` (list of B ints) overrides the drawn lengths (directed edge cases).
+    `temperature`: the old / reference log-probs are centred on the policy softmax(W x / temperature).
     """
     if isinstance(cfg, str):
         cfg = CONFIGS[cfg]
@@ -231,7 +232,7 @@ def make_rollouts(cfg: RolloutConfig | str, device="cpu", layout: str = "padded"
         w = weight[ids[s:e].long()].to(torch.float32)
         zy = (x * w).sum(1)
         s2 = (weight_std ** 2) * (x * x).sum(1)
-        approx[s:e] = zy - math.log(V) - 0.5 * s2
+        approx[s:e] = zy / temperature - math.log(V) - 0.5 * s2 / temperature ** 2
     old = approx + noise * normal(cfg.seed, _T_OLD, 0, R, dev)
     ref = approx + noise * normal(cfg.seed, _T_REF, 0, R, dev)
     log_z = normal(cfg.seed, _T_LOGZ, 0, P, "cpu")

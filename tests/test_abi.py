@@ -104,7 +104,8 @@ def test_null_and_range_errors_are_rejected_on_the_host(lib):
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(clip_eps=1.5)), 0, C.byref(out), None, 0, None) == 4
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(adv_std_ddof=2)), 0, C.byref(out), None, 0, None) == 4
     for bad in (dict(clip_eps_high=-0.1), dict(aggregation=2), dict(ratio_level=3), dict(flow_weight_norm=-1),
-                dict(ratio_level="sequence", aggregation="token")):
+                dict(ratio_level="sequence", aggregation="token"), dict(temperature=-1.0), dict(temperature=float("inf")),
+                dict(temperature=float("nan"))):
         assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(binding.make_params(**bad)), 0, C.byref(out), None, 0, None) == 4, bad
     out.d_hidden = fake                                                                                   # d_weight missing
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), None, 0, None) == 1
@@ -113,6 +114,9 @@ def test_null_and_range_errors_are_rejected_on_the_host(lib):
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), 0x1001, 1 << 40, None) == 5  # misaligned
     assert lib.rl_policy_loss_fwd_bwd(C.byref(b), C.byref(prm), 0, C.byref(out), 0x1000, 16, None) == 5   # too small
     assert lib.rl_token_logprob(C.byref(b), fake, None, 0x1000, 16, None) == 5
+    for bad_t in (0.0, -2.0, float("inf"), float("nan")):
+        assert lib.rl_token_logprob_tempered(C.byref(b), bad_t, fake, None, 0x1000, 1 << 40, None) == 4, bad_t
+    assert lib.rl_token_logprob_tempered(C.byref(b), 0.7, fake, None, 0x1000, 16, None) == 5
     assert b"workspace" in lib.rl_status_string(5)
 
 

@@ -222,6 +222,42 @@ def test_objective_variants_bf16_both_backward_modes(mode):
             _say("  variant", objective, mode, o_opts, err)
 
 
+# --------------------------------------------------------------------------- temperature
+@pytest.mark.parametrize("tau", [0.7, 1.6])
+def test_temperature_f32(tau):
+    b = synth.make_rollouts("tiny", "cuda", "padded", noise=0.3, temperature=tau)
+    for objective in ("grpo", "flow"):
+        ref = run_oracle(b, objective, temperature=tau)
+        res = run_gpu(b, objective, temperature=tau)
+        err = compare_all(b, res, ref, **F32_TOL)
+        st = res.stats_dict()
+        assert abs(st["n_clip_hi"] - ref["n_clip_hi"]) <= 1 and abs(st["n_clip_lo"] - ref["n_clip_lo"]) <= 1
+        _say("  temperature", tau, objective, err)
+    # the scoring call under the same temperature
+    lp, lse = binding.rl_token_logprob_tempered(b.hidden, b.weight, b.token_ids, b.mask, tau, b.cu_seqlens)
+    torch.cuda.synchronize()
+    inp = oracle_inputs(b)
+    rlp, rlse = orc.token_logprob(inp["hidden"], inp["weight"], inp["token_ids"], inp["mask"], temperature=tau)
+    assert np.abs(f64(lp) - rlp).max() <= 2e-5 and np.abs(f64(lse) - rlse).max() <= 2e-5
+
+
+@pytest.mark.parametrize("mode", ["recompute", "stash"])
+def test_temperature_bf16_both_backward_modes(mode):
+    tau = 0.8
+    b = synth.make_rollouts("small", "cuda", "padded", len_div=16, noise=0.3, temperature=tau)
+    for objective in ("grpo", "flow"):
+        ref = run_oracle(b, objective, temperature=tau)
+        res = run_gpu(b, objective, chunk_rows=1024, mode=mode, temperature=tau)
+        err = compare_all(b, res, ref, **BF16_TOL)
+        _say("  temperature", tau, objective, mode, err)
+    # temperature 1 given explicitly is the default path, bit for bit
+    b1 = synth.make_rollouts("small", "cuda", "padded", len_div=16)
+    a = run_gpu(b1, "grpo", chunk_rows=1024, mode=mode)
+    c = run_gpu(b1, "grpo", chunk_rows=1024, mode=mode, temperature=1.0)
+    for x, y in ((a.loss, c.loss), (a.logprob, c.logprob), (a.d_hidden, c.d_hidden), (a.d_weight, c.d_weight)):
+        assert torch.equal(x, y)
+
+
 def test_stash_mode_with_wild_old_logprobs():
     # the single-pass backward takes its reference from the old log-probs: values far from the current policy
     # (here -70 .. +5 nats) must cost range only, never correctness
