@@ -143,8 +143,9 @@ struct EpiFwd {
 //      Every token has a reference ref_t close to its logsumexp, known before the contraction
 //      (target logit minus the old policy's log-prob), so e = exp(z - ref_t) needs no running
 //      maximum: the epilogue adds up s = sum e and u = sum e z per token and tile row, and
-//      stores e itself in the input precision, token-major E[t][v] and vocab-major ET[v][t] (16-byte
-//      stores through the same relabelling as EpiDS).  bf16 keeps f32's exponent range, so e is
+//      stores e itself in the input precision, token-major E[t][v] (16-byte stores through the same
+//      relabelling as EpiDS; the weight-gradient contraction reads E as a K-major operand, so no
+//      vocab-major copy is kept).  bf16 keeps f32's exponent range, so e is
 //      stored at full relative precision whatever its size.  Later, with Z_t = sum_v e,
 //      dS[t][v] = -(c_t / Z_t) (E[t][v] - Z_t 1[v = y_t]): the backward contractions run on E
 //      directly, with the target entry patched and the factor applied per token.
@@ -167,11 +168,10 @@ struct EpiFwdStash {
   float2* part;           // [tiles_m(V)][ldp] partial (s, u) per token of the chunk
   int ldp;
   T* E;  int64_t ld_e;    // [chunk rows][Vp = ld_e], slab-tiled
-  T* ET; int64_t ld_et;   // [Vp][chunk rows = ld_et], slab-tiled
   int V;
   float zs;               // inverse temperature: z = zs * (W x_t) is the logit that ref_t, s and u refer to
 
-  // Exponentials, sums and the two stores, in two rounds of four block rows (64 vocabulary entries = one 128-byte
+  // Exponentials, sums and the stores, in two rounds of four block rows (64 vocabulary entries = one 128-byte
   // line of a token's E row).  A lane holds 16 bytes of the first half of that line (block rows 4j, 4j+1) and 16 of
   // the second (4j+2, 4j+3), and its four lane groups make each half 64 bytes wide; lane pairs (token columns cc,
   // cc^1) swap one half each, so that one store instruction writes whole lines: the eight lanes of the even token's
@@ -183,7 +183,6 @@ struct EpiFwdStash {
     const float zs_l2e = zs * kLog2e;
 #pragma unroll
     for (int j = 0; j < MB / 4; ++j) {
-      bf16x2 et[16][NB / 2];                              // [vocab entry of the round][token pair]: the transposed copy, packed
 #pragma unroll
       for (int bj = 0; bj < NB; ++bj) {
         bf16x8 half[2];
@@ -198,7 +197,6 @@ struct EpiFwdStash {
             sm[bj] += v;
             su[bj] = __builtin_fmaf(v, z, su[bj]);
             half[kk][i] = (bf16_t)v;
-            et[kk * 8 + i][bj >> 1][bj & 1] = (bf16_t)v;
           }
         }
         const u32x4_t a = __builtin_bit_cast(u32x4_t, half[0]), b = __builtin_bit_cast(u32x4_t, half[1]);
@@ -211,14 +209,7 @@ struct EpiFwdStash {
         store_stream(E + tiled_index(c.n0 + perm_col(bj, cc & ~1), v0, ld_e), __builtin_bit_cast(bf16x8, d_even));
         store_stream(E + tiled_index(c.n0 + perm_col(bj, cc | 1), v0, ld_e), __builtin_bit_cast(bf16x8, d_odd));
       }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        bf16x8 col;
-#pragma unroll
-        for (int bj = 0; bj < NB; ++bj) col[bj] = et[r][bj >> 1][bj & 1];
-        store_stream(ET + tiled_index(c.m0 + (2 * j + (r >> 3)) * 32 + g * 8 + (r & 7), c.n0 + cc * 8, ld_et), col);
-      }
-      __builtin_amdgcn_sched_barrier(0);                  // keep the two rounds apart: 128 live values each is plenty
+      __builtin_amdgcn_sched_barrier(0);                  // keep the two rounds apart
     }
   }
 
@@ -267,14 +258,13 @@ template <> struct Pack4<float> {
 
 // ---- backward, stage 1: recomputed logits -> dS = zs c_t (1[v=y_t] - exp(z - lse_t)) (z the tempered
 //      logit, zs = 1 / temperature the chain factor back to W x_t), formed in
-//      f32 (subtraction and scaling before rounding) and stored in the input precision twice:
-//      token-major dS[t][v] (operand of dX = dS W) and vocab-major dST[v][t] (operand of
-//      dW = dS^T X), so that both later contractions have K contiguous.
+//      f32 (subtraction and scaling before rounding) and stored in the input precision, token-major
+//      dS[t][v] (operand of dX = dS W).  dW = dS^T X reads the same array as a K-major operand in the
+//      bf16 hot kernel; f32 inputs (generic kernel) also get the vocab-major copy dST[v][t].
 //
 //      In the hot kernel (16x16 blocks) the tile rows and columns are relabelled (kPermute, see
 //      perm_row / perm_col in gemm_nt.h) such that a lane ends up holding eight consecutive
-//      vocabulary entries of a token and eight consecutive tokens of a vocabulary entry: both
-//      copies then leave in 16-byte stores, 64 per wavefront and tile, with no staging through LDS.
+//      vocabulary entries of a token: the copy leaves in 16-byte stores with no staging through LDS.
 template <class T>
 struct EpiDS {
   typedef NoPre Pre;
@@ -283,9 +273,9 @@ struct EpiDS {
   __device__ void keep_alive() const { dS[0] = (T)0.f; }
   const int* ids_c; const float* lse_c; const float* c_c;
   T* dS;  int64_t ld_ds;    // [chunk rows][Vp]
-  T* dST; int64_t ld_dst;   // [Vp][chunk rows]
+  T* dST; int64_t ld_dst;   // [Vp][chunk rows]; f32 inputs only
   int V;
-  bool tiled;               // both copies slab-tiled (always so for bf16: their consumer is the hot kernel)
+  bool tiled;               // dS slab-tiled (always so for bf16: its consumer is the hot kernel)
   float zs;                 // inverse temperature
 
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
@@ -334,13 +324,6 @@ struct EpiDS {
           store_stream(dS + tiled_index(c.n0 + perm_col(bj, cc & ~1), v0, ld_ds), __builtin_bit_cast(bf16x8, d_even));
           store_stream(dS + tiled_index(c.n0 + perm_col(bj, cc | 1), v0, ld_ds), __builtin_bit_cast(bf16x8, d_odd));
         }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          bf16x8 v;
-#pragma unroll
-          for (int bj = 0; bj < NB; ++bj) v[bj] = o[bj][r];
-          store_stream(dST + tiled_index(c.m0 + (2 * j + (r >> 3)) * 32 + g * 8 + (r & 7), c.n0 + cc * 8, ld_dst), v);
-        }
       }
     } else {
 #pragma unroll
@@ -364,8 +347,10 @@ struct EpiDS {
               o[e] = (valid && (m + e) < V) ? ds : 0.f;
             }
             Pack4<T>::store(dS + operand_index(tiled, n, m, ld_ds), o[0], o[1], o[2], o[3]);
+            if constexpr (sizeof(T) == 4) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) dST[operand_index(tiled, m + e, n, ld_dst)] = (T)o[e];
+              for (int e = 0; e < 4; ++e) dST[operand_index(tiled, m + e, n, ld_dst)] = (T)o[e];
+            }
           }
       }
     }

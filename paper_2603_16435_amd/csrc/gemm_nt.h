@@ -307,11 +307,28 @@ __device__ __attribute__((always_inline)) inline void mfma_drain() { asm volatil
 // are issued after MFMA number VMO, VMO + VMG, VMO + 2 VMG, ...
 constexpr int kHotStageBytes = (256 + 256) * kSlabBytes;      // one LDS stage of the hot kernel: a slab of A and of B
 
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, the four 16-bit values that lane
+// 4e + j/4 fetched (8 bytes at its own address) are dealt to lanes 4(j/4).. : lane j receives, as element e,
+// value j%4 of the piece fetched by lane 4e + j/4.  With lanes 4e..4e+3 pointing at sixteen consecutive m of
+// k-row e, lane j ends up with (m = j, k = 0..3): an MFMA operand read out of a K-major slab.
+typedef short tr16x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __attribute__((always_inline)) inline u32x2_t lds_read_tr16(const unsigned char* p) {
+  typedef __attribute__((address_space(3))) tr16x4_t* lds_ptr;
+  return __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p)));
+}
+
 // The work of one workgroup of the hot kernel: tile number `pid` of the contraction (A, B, d) into epi.
 // stage0 / stage1 are the caller's two LDS stages; they must be separate objects so that the compiler
 // can tell the stage being filled by the DMA loads from the stage the fragments are read from and
 // does not serialise them with a vmcnt(0).
-template <class Epi, int PFD, int VMG, int VMO>
+//
+// ATR: the A operand is given K-major, element (m, k) at tiled_index(k, m, d.lda) (the slab-tiled layout of its
+// transpose, whose rows are k): C = A^T-stored x B without a transposed copy of A in memory.  Its LDS slab is
+// 64 k-rows of 256 m (512 bytes a row, 32-byte pieces XOR-swizzled by a function of the row such that the eight
+// rows a half-wavefront's transposing read touches fall into different banks) and its fragments come from two
+// transposing reads each.
+template <class Epi, int PFD, int VMG, int VMO, bool ATR = false>
 __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d,
                                                                         const Epi& epi, int pid, unsigned char* stage0, unsigned char* stage1) {
   constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2;
@@ -343,18 +360,31 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   for (int j = 0; j < 8; ++j) {
     const int lr = wave * 64 + j * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((lr >> 1) & 7);
-    int r = tm * BM + (Epi::kPermute ? perm_lds_row_a(lr) : lr); r = r < M ? r : M - 1;
-    if (d.a_rows) r = d.a_rows[r];
-    ap[j] = A + (d.a_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.lda) + c * 8;
+    int r;
+    if constexpr (ATR) {
+      const int p = (wave * 8 + j) * 64 + lane;                  // 16-byte unit of the A slab this lane fills
+      const int row = p >> 5, u = p & 31;                        // k-row of the slab, unit inside the row
+      const int f = (row & 3) | (((row >> 3) & 1) << 2);
+      const int m = tm * BM + (((u >> 1) ^ f) << 4) + ((u & 1) << 3);
+      ap[j] = A + tiled_index(row, m, d.lda);
+    } else {
+      r = tm * BM + (Epi::kPermute ? perm_lds_row_a(lr) : lr); r = r < M ? r : M - 1;
+      if (d.a_rows) r = d.a_rows[r];
+      ap[j] = A + (d.a_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.lda) + c * 8;
+    }
     r = tn * BN + (Epi::kPermute ? perm_lds_row_b(lr) : lr); r = r < N ? r : N - 1;
     if (d.b_rows) r = d.b_rows[r];
     bp[j] = B + (d.b_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.ldb) + c * 8;
   }
   const int a_ks = d.a_tiled ? 16384 : BK, b_ks = d.b_tiled ? 16384 : BK;     // elements from one slab to the next
+  // K-major A: slab s is k-rows [64 s, 64 s + 64), i.e. quarter s%4 of row block s/4 of the tiled layout
+  auto a_slab = [&](int slab) __attribute__((always_inline)) -> int64_t {
+    return ATR ? (int64_t)(slab >> 2) * (d.lda * 256) + (slab & 3) * 4096 : (int64_t)slab * a_ks;
+  };
   // load j of the 16 per slab (0..7 = A rows, 8..15 = B rows)
   auto issue1 = [&](int slab, unsigned char* stage, int j) __attribute__((always_inline)) {
     unsigned char* as = stage + wave * 64 * kSlabBytes;
-    if (j < 8) load16_to_lds(ap[j] + (int64_t)slab * a_ks, as + j * 8 * kSlabBytes);
+    if (j < 8) load16_to_lds(ap[j] + a_slab(slab), as + j * 8 * kSlabBytes);
     else load16_to_lds(bp[j - 8] + (int64_t)slab * b_ks, as + A_BYTES + (j - 8) * 8 * kSlabBytes);
   };
 
@@ -365,7 +395,12 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   // instruction on one fixed line (no divergent control flow around the accumulators).
   const unsigned char* pf_ptr;
   int pf_stride;
-  if (wave == 0) {
+  const bool pf_atr = ATR && wave == 0;
+  if (pf_atr) {                                    // K-major A: the slab's 256 lines are (k-row, 64-m block); a quarter per N-tile
+    const int q = 64 * (tn & 3) + lane;
+    pf_ptr = reinterpret_cast<const unsigned char*>(A + tiled_index(q >> 2, tm * BM + 64 * (q & 3), d.lda));
+    pf_stride = 0;
+  } else if (wave == 0) {
     int r = tm * BM + 64 * (tn & 3) + lane; r = r < M ? r : M - 1;
     if (d.a_rows) r = d.a_rows[r];
     pf_ptr = reinterpret_cast<const unsigned char*>(A + (d.a_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.lda));
@@ -384,7 +419,7 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
     if (PFD > 0) {
       pf_sink ^= slot;                                   // fetched two slabs ago: long since back
       const int k = kt + PFD < nk ? kt + PFD : nk - 1;
-      slot = *reinterpret_cast<const unsigned*>(pf_ptr + (int64_t)k * pf_stride);
+      slot = *reinterpret_cast<const unsigned*>(pf_ptr + (int64_t)k * pf_stride + (pf_atr ? a_slab(k) * 2 : 0));
     }
   };
 
@@ -410,6 +445,19 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   const int arow = (wm * WM + frow) * kSlabBytes, brow = A_BYTES + (wn * WN + frow) * kSlabBytes;
   const int swz = (frow >> 1) & 7;                 // the other row blocks are 16 rows apart: same swizzle
   u32x4_t fa[2][MB], fb[2][NB / 2];
+  // K-major A: byte offset, in the slab, of the 8-byte piece this lane points a transposing read of block bi at:
+  // k-row 8 (l/16) + (l%16)/4 of the k-step, 32-byte chunk (8 wm + bi) ^ f(row), piece l%4
+  int atr_base[MB];
+  if constexpr (ATR) {
+    const int f = ((frow >> 2) & 3) | ((fq & 1) << 2);
+#pragma unroll
+    for (int i = 0; i < MB; ++i) atr_base[i] = (8 * fq + (frow >> 2)) * 512 + (((wm * 8 + i) ^ f) << 5) + ((frow & 3) << 3);
+  }
+  // half h (k = 0..3 or 4..7 of the lane's eight) of A block i of k-step fs
+  auto read_a_tr = [&](u32x4_t& dst, const unsigned char* fstage, int i, int fs, int h) __attribute__((always_inline)) {
+    const u32x2_t v = lds_read_tr16(fstage + atr_base[i] + (32 * fs + 4 * h) * 512);
+    dst[2 * h] = v[0]; dst[2 * h + 1] = v[1];
+  };
   auto kof = [&](int k) __attribute__((always_inline)) { return k < nk ? k : nk - 1; };   // slab number; past the end: harmless re-load
 
   // One phase = 32 MFMAs on (fa[aset], fb[bset]) into column half `half`, with, at fixed places between them,
@@ -423,7 +471,10 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
 #pragma unroll
     for (int q = 0; q < 32; ++q) {
       mfma16(acc[q >> 2][half * 4 + (q & 3)], fa[aset][q >> 2], fb[bset][q & 3]);
-      if (q % DSG == 0 && q / DSG < kind) {
+      if (ATR && kind == 12) {                          // sixteen half-reads of A, one per MFMA, then the four of B
+        if (q < 16) read_a_tr(fa[aset ^ 1][q >> 1], fstage, q >> 1, fs, q & 1);
+        else if (q % DSG == 0 && q < 24) fb[bset ^ 1][(q - 16) / DSG] = *reinterpret_cast<const u32x4_t*>(fstage + brow + ((q - 16) / DSG) * 16 * kSlabBytes + slot);
+      } else if (q % DSG == 0 && q / DSG < kind) {
         const int f = q / DSG;
         if (kind == 4) fb[bset ^ 1][f] = *reinterpret_cast<const u32x4_t*>(fstage + brow + (4 + f) * 16 * kSlabBytes + slot);
         else if (f < 8) fa[aset ^ 1][f] = *reinterpret_cast<const u32x4_t*>(fstage + arow + f * 16 * kSlabBytes + slot);
@@ -457,7 +508,10 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
     {
       const int slot = (fq ^ swz) << 4;
 #pragma unroll
-      for (int i = 0; i < MB; ++i) fa[0][i] = *reinterpret_cast<const u32x4_t*>(stage0 + arow + i * 16 * kSlabBytes + slot);
+      for (int i = 0; i < MB; ++i) {
+        if constexpr (ATR) { read_a_tr(fa[0][i], stage0, i, 0, 0); read_a_tr(fa[0][i], stage0, i, 0, 1); }
+        else fa[0][i] = *reinterpret_cast<const u32x4_t*>(stage0 + arow + i * 16 * kSlabBytes + slot);
+      }
 #pragma unroll
       for (int j = 0; j < NB / 2; ++j) fb[0][j] = *reinterpret_cast<const u32x4_t*>(stage0 + brow + j * 16 * kSlabBytes + slot);
     }
@@ -474,25 +528,26 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   if (PFD > 0 && (pf_sink ^ pf0 ^ pf1) == 0x9E3779B9u && K < 0) epi.keep_alive();   // never true: keeps the prefetch loads
 }
 
-template <class Epi, int PFD, int VMG, int VMO>
+template <class Epi, int PFD, int VMG, int VMO, bool ATR = false>
 __global__ __launch_bounds__(256)
 void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, Epi epi) {
   __shared__ __attribute__((aligned(1024))) unsigned char stage0[kHotStageBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char stage1[kHotStageBytes];
-  gemm_nt_bf16_tile<Epi, PFD, VMG, VMO>(A, B, d, epi, blockIdx.x, stage0, stage1);
+  gemm_nt_bf16_tile<Epi, PFD, VMG, VMO, ATR>(A, B, d, epi, blockIdx.x, stage0, stage1);
 }
 
 // Two independent contractions in one launch: workgroups [0, n1) work on the first, the rest on the
 // second.  Used where one of them alone has too few tiles to fill the last round of the 256 CUs: the
 // other's workgroups then fill the tail.  n1 must be a multiple of the XCD count (tile order).
-template <class Epi1, int PFD1, int VMG1, int VMO1, class Epi2, int PFD2, int VMG2, int VMO2>
+// ATR2: the second contraction's A operand is given K-major (see gemm_nt_bf16_tile).
+template <class Epi1, int PFD1, int VMG1, int VMO1, class Epi2, int PFD2, int VMG2, int VMO2, bool ATR2 = false>
 __global__ __launch_bounds__(256)
 void gemm_nt_bf16_pair_kernel(const bf16_t* __restrict__ A1, const bf16_t* __restrict__ B1, GemmDims d1, Epi1 epi1, int n1,
                               const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2, GemmDims d2, Epi2 epi2) {
   __shared__ __attribute__((aligned(1024))) unsigned char stage0[kHotStageBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char stage1[kHotStageBytes];
   if ((int)blockIdx.x < n1) gemm_nt_bf16_tile<Epi1, PFD1, VMG1, VMO1>(A1, B1, d1, epi1, blockIdx.x, stage0, stage1);
-  else gemm_nt_bf16_tile<Epi2, PFD2, VMG2, VMO2>(A2, B2, d2, epi2, (int)blockIdx.x - n1, stage0, stage1);
+  else gemm_nt_bf16_tile<Epi2, PFD2, VMG2, VMO2, ATR2>(A2, B2, d2, epi2, (int)blockIdx.x - n1, stage0, stage1);
 }
 
 }  // namespace rlk

@@ -28,7 +28,8 @@
 namespace rlk {
 
 constexpr int kDefaultChunkRows = 32768;        // recompute mode: 128 x 14 dX tiles = 7 full rounds of 256 CUs on the 7B shape
-constexpr int kDefaultChunkRowsStash = 49152;   // single-pass mode: longer K for dW, dX bands divide evenly over the XCDs (measured +2-4 %)
+constexpr int kDefaultChunkRowsStash = 49152;
+   // single-pass mode: longer K for dW, dX bands divide evenly over the XCDs (measured +2-4 %)
 constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
 constexpr int kGemmThreads = kWavesM * kWavesN * 64;
 constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 KiB per CU
@@ -326,7 +327,7 @@ __global__ void lse_sum_kernel(const float2* part, int ldp, int tiles_v, const f
 template <class T>
 __global__ void stash_patch_kernel(const ChunkDesc* desc, const int32_t* ids_c, const float* zy_c, const float* ref_l2e,
                                    const float* zsum_c, const float* c_c, float inv_tau, float* row_scale,
-                                   T* E, int64_t ld_e, T* ET, int64_t ld_et) {
+                                   T* E, int64_t ld_e) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= desc->rows) return;
   const int g = desc->row_start + n;
@@ -336,7 +337,6 @@ __global__ void stash_patch_kernel(const ChunkDesc* desc, const int32_t* ids_c, 
   const T v = (T)(ey - Z);
   const int y = ids_c[g];
   E[tiled_index(n, y, ld_e)] = v;
-  ET[tiled_index(y, n, ld_et)] = v;
 }
 
 // ------------------------------------------------------------------ forward combine
@@ -669,7 +669,7 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
     p.off_wt = take(p.esz * Hp * (size_t)p.Vp);
     p.off_xt = take(p.esz * Hp * (size_t)tc);
     p.off_ds = take(p.esz * (size_t)tc * (size_t)p.Vp);
-    p.off_dst = take(p.esz * (size_t)p.Vp * (size_t)tc);
+    if (b->dtype == RL_F32) p.off_dst = take(p.esz * (size_t)p.Vp * (size_t)tc);   // bf16: dW reads dS / E itself
   }
   p.off_desc = p.off_ref = p.off_zsum = p.off_scale = 0;
   if (p.stash) {
@@ -706,6 +706,15 @@ template <class Tune, class Epi>
 static void launch_gemm(const float* A, const float* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
   const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
   launch_generic<float, Epi>(A, B, d, epi, tiles, s);
+}
+
+// Weight-gradient contraction of the recompute mode: bf16 reads dS (K-major A operand), f32 its stored transpose.
+static void launch_dw(const bf16_t* dS, const bf16_t*, const bf16_t* XT, const GemmDims& d, const EpiDW& epi, hipStream_t s) {
+  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  gemm_nt_bf16_kernel<EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo, true><<<tiles, 256, 0, s>>>(dS, XT, d, epi);
+}
+static void launch_dw(const float*, const float* dST, const float* XT, const GemmDims& d, const EpiDW& epi, hipStream_t s) {
+  launch_gemm<TuneDW>(dST, XT, d, epi, s);
 }
 
 struct Ptrs {
@@ -801,14 +810,15 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       ProfScope ps(RL_PROF_GEMM_DX, s);
       launch_gemm<TuneDX>(dS, WT, d, e, s);
     }
-    {  // dW (+)= dS^T X : A = dS^T [Vp][Tc], B = X^T [H][Tc]
+    {  // dW (+)= dS^T X : B = X^T [H][Tc]; A = dS^T, for bf16 read out of dS itself as a K-major operand
+       // (K = Tc is a multiple of 256 and the workspace is aligned: always the hot kernel), for f32 the stored copy [Vp][Tc]
       GemmDims d{};
-      d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.Tc; d.ldb = p.Tc;
+      d.M = p.V; d.N = p.H; d.K = p.Tc; d.lda = p.tiled ? p.Vp : p.Tc; d.ldb = p.Tc;
       d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 3; d.group_m = TuneDW::kBand; d.a_tiled = d.b_tiled = p.tiled;
       d.zero_if_empty = (ch == 0);
       EpiDW e{d_weight, p.H, p.V, p.H, ch > 0 ? 1 : 0};
       ProfScope ps(RL_PROF_GEMM_DW, s);
-      launch_gemm<TuneDW>(dST, XT, d, e, s);
+      launch_dw(dS, dST, XT, d, e, s);
     }
   }
 }
@@ -835,7 +845,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
   const T* X = static_cast<const T*>(b->hidden);
   const T* W = static_cast<const T*>(b->weight);
   T* WT = static_cast<T*>(q.wt); T* XT = static_cast<T*>(q.xt);
-  T* E = static_cast<T*>(q.ds); T* ET = static_cast<T*>(q.dst);
+  T* E = static_cast<T*>(q.ds);
   T* dX = static_cast<T*>(out->d_hidden);
   {
     ProfScope ps(RL_PROF_TRANSPOSE, s);
@@ -853,11 +863,11 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
   for (int k = 0; k < p.n_desc; ++k) {
     const ChunkDesc* dk = q.desc + k;
     const int* chunk = &dk->row_start;
-    {  // forward: partial sums + E, E^T
+    {  // forward: partial sums + E
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
       d.b_rows = q.row_map; d.chunk = chunk; d.dyn = 2; d.group_m = TuneLogits::kBand;
-      EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, ET, p.Tc, p.V, p.inv_tau};
+      EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, p.V, p.inv_tau};
       ProfScope ps(RL_PROF_GEMM_FWD, s);
       gemm_nt_bf16_kernel<EpiFwdStash<T>, TuneLogits::kPfd, TuneLogits::kVmg, TuneLogits::kVmo>
           <<<((p.V + kBM - 1) / kBM) * ((p.Tc + kBN - 1) / kBN), 256, 0, s>>>(W, X, d, e);
@@ -872,29 +882,30 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       seq_loss_kernel<<<p.B, 256, 0, s>>>(objective, q.logp_c, b->old_logprob, b->ref_logprob, q.row_map, q.cstart, q.adv,
                                          b->group_idx, b->log_z, p.B, loss_opts(prm), q.ctrl,
                                          q.seq_loss, q.gterm, q.c_c, out->coeff, out->stats, dk);
-      stash_patch_kernel<T><<<(p.Tc + 255) / 256, 256, 0, s>>>(dk, q.ids_c, q.zy, q.ref, q.zsum, q.c_c, p.inv_tau, q.scale, E, p.Vp, ET, p.Tc);
+      stash_patch_kernel<T><<<(p.Tc + 255) / 256, 256, 0, s>>>(dk, q.ids_c, q.zy, q.ref, q.zsum, q.c_c, p.inv_tau, q.scale, E, p.Vp);
     }
     {  // X^T chunk scaled by -c/Z, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
       transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc, true);
     }
-    {  // dX = diag(-c/Z) E' W  (A = E' [Tc][Vp], B = W^T [H][Vp]) and dW (+)= E'^T (diag(-c/Z) X)  (A = E'^T [Vp][Tc],
-       // B = scaled X^T [H][Tc]) in one launch: dX alone has too few (long) tiles to fill its last round of CUs
+    {  // dX = diag(-c/Z) E' W  (A = E' [Tc][Vp], B = W^T [H][Vp]) and dW (+)= E'^T (diag(-c/Z) X)  (A = E'^T, read out
+       // of E' itself as a K-major operand; B = scaled X^T [H][Tc]) in one launch: dX alone has too few (long) tiles
+       // to fill its last round of CUs
       GemmDims dx{};
       dx.M = p.Tc; dx.N = p.H; dx.K = p.Vp; dx.lda = p.Vp; dx.ldb = p.Vp;
       dx.chunk = chunk; dx.dyn = 1; dx.group_m = TuneDX::kBand; dx.a_tiled = dx.b_tiled = 1;
       EpiDX<T> ex{q.row_map, dX, p.H, p.H, q.scale};
       GemmDims dw{};
-      dw.M = p.V; dw.N = p.H; dw.K = p.Tc; dw.lda = p.Tc; dw.ldb = p.Tc;
+      dw.M = p.V; dw.N = p.H; dw.K = p.Tc; dw.lda = p.Vp; dw.ldb = p.Tc;
       dw.chunk = chunk; dw.dyn = 3; dw.zero_if_empty = (k == 0); dw.group_m = TuneDW::kBand; dw.a_tiled = dw.b_tiled = 1;
       EpiDW ew{out->d_weight, p.H, p.V, p.H, k > 0 ? 1 : 0};
       const int tn = (p.H + kBN - 1) / kBN;
       const int n1 = (((p.Tc + kBM - 1) / kBM) * tn + kXcds - 1) / kXcds * kXcds;
       const int n2 = ((p.V + kBM - 1) / kBM) * tn;
       ProfScope ps(RL_PROF_GEMM_BWD, s);
-      gemm_nt_bf16_pair_kernel<EpiDX<T>, TuneDX::kPfd, TuneDX::kVmg, TuneDX::kVmo, EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo>
-          <<<n1 + n2, 256, 0, s>>>(E, WT, dx, ex, n1, ET, XT, dw, ew);
+      gemm_nt_bf16_pair_kernel<EpiDX<T>, TuneDX::kPfd, TuneDX::kVmg, TuneDX::kVmo, EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo, true>
+          <<<n1 + n2, 256, 0, s>>>(E, WT, dx, ex, n1, E, XT, dw, ew);
     }
   }
   ProfScope ps(RL_PROF_LOSS, s);
