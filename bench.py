@@ -24,9 +24,9 @@ PEAK_F32_TFLOPS = 157.3
 # HBM-side bytes (L2 <-> fabric; FETCH_SIZE x2.0 + WRITE_SIZE x1.0 after calibration against a plain 1 GiB copy)
 # of the largest launch of each contraction class on the default workload, from two rocprofv3 --pmc runs per
 # backward mode whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
-MEASURED_TRAFFIC_7B = {        # default chunks: 49152 rows single-pass ("stash"), 32768 rows recompute
-    "stash": {"gemm_fwd": 114.1e9 + 29.8e9, "gemm_bwd": 258.6e9 + 2.5e9},
-    "recompute": {"gemm_fwd": 60.7e9 + 0.3e9, "gemm_ds": 68.9e9 + 20.2e9, "gemm_dx": 61.5e9 + 0.2e9, "gemm_dw": 71.6e9 + 2.2e9},
+MEASURED_TRAFFIC_7B = {        # default chunks: 40960 rows single-pass ("stash"), 32768 rows recompute
+    "stash": {"gemm_fwd": 98.8e9 + 12.7e9, "gemm_bwd": 218.7e9 + 2.5e9},
+    "recompute": {"gemm_fwd": 55.9e9 + 0.3e9, "gemm_ds": 63.0e9 + 10.0e9, "gemm_dx": 69.4e9 + 0.2e9, "gemm_dw": 76.5e9 + 2.2e9},
 }
 CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 8, "7b": 160, "long": 640, "32b": 768}   # ~10-30 s of oracle work
 
@@ -214,7 +214,8 @@ def main():
 
     # launches per step that have rows to work on (the library launches a fixed upper bound of chunks; the rest return at once)
     stash = prof["gemm_bwd"][1] > 0
-    tc = a.chunk_rows or (49152 if stash else binding.lib().rl_default_chunk_rows())
+    default_tc = binding.lib().rl_default_chunk_rows_single_pass() if stash else binding.lib().rl_default_chunk_rows()
+    tc = a.chunk_rows or default_tc
     if stash:                                  # sequence-aligned chunks: greedy packing of whole sequences
         real_chunks, rows = 1, 0
         for n in b.lengths.tolist():
@@ -256,7 +257,7 @@ def main():
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": (MEASURED_TRAFFIC_7B["stash" if stash else "recompute"].get(dom)
                                  if (a.config == "7b" and a.len_div == 1 and a.layout == "padded"
-                                     and tc == (49152 if stash else 32768)) else None),
+                                     and tc == default_tc) else None),
                      "traffic_note": "HBM-side bytes of the largest launch of this class (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
                      "launches_with_work": real_chunks * a.steps, "launches": int(dom_n),
                      "avg_launch_ms": dom_ms / max(real_chunks * a.steps, 1),

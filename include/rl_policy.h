@@ -102,7 +102,7 @@ typedef struct rl_params {
   float   beta;                 /* FLOW only: reward scale                               */
   float   adv_eps;              /* added to the group std                                */
   int32_t adv_std_ddof;         /* 0 (population std) or 1                               */
-  int32_t chunk_rows;           /* rows staged at once; 0 = library default (32768; 49152 in single-pass mode) */
+  int32_t chunk_rows;           /* rows staged at once; 0 = library default (32768; 40960 in single-pass mode) */
                                 /* rounded up to a multiple of 256; sizes the workspace  */
   float   clip_eps_high;        /* upper bound of the ratio / weight is 1 + clip_eps_high; 0 = clip_eps (symmetric) */
   int32_t aggregation;          /* GRPO: RL_AGG_SEQUENCE (mean over sequences of the token mean) or         */
@@ -182,7 +182,7 @@ enum { RL_PROF_PREP = 0,       /* counts, scan, compaction, output zero-fill    
        RL_PROF_COMBINE = 2,    /* partials -> lse, logp                                 */
        RL_PROF_LOSS = 3,       /* advantage, per-sequence loss, final reduce            */
        RL_PROF_TRANSPOSE = 4,  /* W^T, X^T chunks, zeroing masked dX rows               */
-       RL_PROF_GEMM_DS = 5,    /* recomputed logits -> dS, dS^T                         */
+       RL_PROF_GEMM_DS = 5,    /* recomputed logits -> dS                               */
        RL_PROF_GEMM_DX = 6,    /* dX = dS W                                             */
        RL_PROF_GEMM_DW = 7,    /* dW += dS^T X                                          */
        RL_PROF_GEMM_BWD = 8,   /* single-pass backward: dX and dW of a chunk in one launch */
@@ -194,9 +194,10 @@ typedef struct rl_profile {     /* host struct */
 void rl_profile_enable(int32_t on);
 rl_status rl_profile_read(rl_profile* out);
 
-/* Library version (major*100 + minor) and the chunk size used when chunk_rows = 0 in recompute mode. */
+/* Library version (major*100 + minor) and the chunk sizes used when chunk_rows = 0 (recompute mode; single-pass mode). */
 int32_t rl_version(void);
 int32_t rl_default_chunk_rows(void);
+int32_t rl_default_chunk_rows_single_pass(void);
 
 /* The log-Z head: the step that produces rl_batch.log_z for the flow-balance objective (the problem
  * statement takes "per-prompt log Z" as given; reading: a two-layer MLP over the mean of the prompt's

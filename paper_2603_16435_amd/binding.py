@@ -108,6 +108,7 @@ def lib() -> C.CDLL:
         L.rl_rvq_encode.restype = C.c_int
         L.rl_version.restype = C.c_int32
         L.rl_default_chunk_rows.restype = C.c_int32
+        L.rl_default_chunk_rows_single_pass.restype = C.c_int32
         _lib = L
     return _lib
 

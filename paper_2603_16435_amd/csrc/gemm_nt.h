@@ -93,22 +93,48 @@ __device__ inline bool resolve_dims(GemmDims& d, int& M, int& N, int& K) {
   return true;
 }
 
-// Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin, and each XCD has its own
-// L2, so ids are first regrouped such that one XCD receives a contiguous run of tile numbers;
-// runs are then laid out in bands of group_m M-tiles by all N-tiles, N fastest inside a band
-// column, so the workgroups resident on one XCD share A and B panels through its L2.
-__device__ inline void tile_of_block(int pid, int tiles_m, int tiles_n, int group_m, int& tm, int& tn) {
-  const int total = tiles_m * tiles_n;
-  const int per = total / kXcds, rem = total % kXcds;
+// Workgroup -> tile.  Workgroups are dealt to the 8 XCDs round-robin (workgroup id % 8), and each XCD has
+// its own L2.  Tiles are walked in bands of group_m M-tiles by all N-tiles, M fastest inside a band column,
+// so that the workgroups resident on one XCD at a time (about group_m M-tiles by 32 / group_m N-tiles)
+// share their A and B panels through its L2.  Two ways of giving each XCD its part of that sequence:
+//
+//  * runs (by_share = false): the sequence is cut into eight equal runs.  The XCDs are then at unrelated
+//    N positions, which spreads their B-panel reads over the memory channels.  Best where the B panels
+//    are short or few enough to live in the memory-side cache (logits: K = H; dW: B = X^T chunk).
+//  * shares (by_share = true): an XCD owns a contiguous share of the M-tiles that exist (after dynamic
+//    trimming; shares differ by at most one tile) and all XCDs are at the same N-tiles at the same
+//    time, so a B panel comes out of memory once and reaches the other XCDs through the memory-side
+//    cache.  Needed for dX, where both operands stream from memory over a very long K (B = W^T, a
+//    1 GB panel set per sweep): equal runs there are 7 % slower unless they happen to start on band
+//    boundaries, and with shares a partly filled chunk is spread over all XCDs instead of the first few.
+//
+// The launch has launch_tiles() workgroups of the static bounds; the ones without a tile get false.
+__device__ __host__ inline int launch_tiles(int tiles_m, int tiles_n) {
+  return (tiles_m + kXcds - 1) / kXcds * kXcds * tiles_n;
+}
+__device__ inline bool tile_of_block(int pid, int tiles_m, int tiles_n, int group_m, bool by_share, int& tm, int& tn) {
   const int xcd = pid % kXcds, q = pid / kXcds;
-  const int t = xcd * per + (xcd < rem ? xcd : rem) + q;
+  int t, first = 0, rows = tiles_m;                // position in the band sequence of `rows` M-tiles starting at `first`
+  if (by_share) {
+    const int base = tiles_m / kXcds, rem = tiles_m % kXcds;
+    rows = base + (xcd < rem ? 1 : 0);
+    first = xcd * base + (xcd < rem ? xcd : rem);
+    if (q >= rows * tiles_n) return false;
+    t = q;
+  } else {
+    const int total = tiles_m * tiles_n;
+    if (pid >= total) return false;
+    const int per = total / kXcds, rem = total % kXcds;
+    t = xcd * per + (xcd < rem ? xcd : rem) + q;
+  }
   const int band = group_m * tiles_n;
   const int g = t / band;
   const int first_m = g * group_m;
-  const int gsz = (tiles_m - first_m < group_m) ? (tiles_m - first_m) : group_m;
+  const int gsz = (rows - first_m < group_m) ? (rows - first_m) : group_m;
   const int r = t - g * band;
-  tm = first_m + r % gsz;
+  tm = first + first_m + r % gsz;
   tn = r / gsz;
+  return true;
 }
 
 __device__ inline int lds_off(int row, int chunk) {           // byte offset inside one operand slab
@@ -191,9 +217,11 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
 
   int M, N, K;
   if (!resolve_dims(d, M, N, K)) return;
-  const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+  // dynamic M (dX): XCD shares of the M-tiles that exist; otherwise equal runs over the static grid
+  const bool by_share = d.dyn == 1;
+  const int tiles_m = ((by_share ? M : d.M) + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   int tm, tn;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, d.group_m, tm, tn);
+  if (!tile_of_block(blockIdx.x, tiles_m, tiles_n, d.group_m, by_share, tm, tn)) return;
   if (tm * BM >= M || tn * BN >= N) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -341,10 +369,11 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   int M, N, K;
   if (!resolve_dims(d, M, N, K)) return;
   const int nk = K / BK;
-  const int tiles_m = (d.M + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
+  // dynamic M (dX): XCD shares of the M-tiles that exist; otherwise equal runs over the static grid
+  const bool by_share = d.dyn == 1;
+  const int tiles_m = ((by_share ? M : d.M) + BM - 1) / BM, tiles_n = (d.N + BN - 1) / BN;
   int tm, tn;
-  if (pid >= tiles_m * tiles_n) return;
-  tile_of_block(pid, tiles_m, tiles_n, d.group_m, tm, tn);
+  if (!tile_of_block(pid, tiles_m, tiles_n, d.group_m, by_share, tm, tn)) return;
   if (tm * BM >= M || tn * BN >= N) return;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -538,7 +567,7 @@ void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict_
 
 // Two independent contractions in one launch: workgroups [0, n1) work on the first, the rest on the
 // second.  Used where one of them alone has too few tiles to fill the last round of the 256 CUs: the
-// other's workgroups then fill the tail.  n1 must be a multiple of the XCD count (tile order).
+// other's workgroups then fill the tail.  n1 = launch_tiles() of the first (a multiple of the XCD count).
 // ATR2: the second contraction's A operand is given K-major (see gemm_nt_bf16_tile).
 template <class Epi1, int PFD1, int VMG1, int VMO1, class Epi2, int PFD2, int VMG2, int VMO2, bool ATR2 = false>
 __global__ __launch_bounds__(256)

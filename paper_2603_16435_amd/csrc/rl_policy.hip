@@ -7,8 +7,8 @@
 //   forward   : per chunk of compacted rows: logits tiles (MFMA) -> partial (max,sumexp) per
 //               vocab tile + target logit -> combine -> lse_t, logp_t
 //   loss      : one workgroup per sequence: length-normalised sums, loss_i, c_t; final reduce
-//   backward  : W^T once; per chunk: X^T, recomputed logits -> dS / dS^T (input precision),
-//               dX = dS W (scattered to original rows), dW (+)= dS^T X
+//   backward  : W^T once; per chunk: X^T, recomputed logits -> dS (input precision; f32 inputs also dS^T),
+//               dX = dS W (scattered to original rows), dW (+)= dS^T X (bf16: dS read as a K-major operand)
 // The number of real rows is only known on the device, so grids are sized for the upper
 // bound R and every kernel trims itself against the device-side count.
 #include <hip/hip_runtime.h>
@@ -28,7 +28,7 @@
 namespace rlk {
 
 constexpr int kDefaultChunkRows = 32768;        // recompute mode: 128 x 14 dX tiles = 7 full rounds of 256 CUs on the 7B shape
-constexpr int kDefaultChunkRowsStash = 49152;
+constexpr int kDefaultChunkRowsStash = 40960;
    // single-pass mode: longer K for dW, dX bands divide evenly over the XCDs (measured +2-4 %)
 constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
 constexpr int kGemmThreads = kWavesM * kWavesN * 64;
@@ -603,7 +603,7 @@ struct Plan {
   int64_t R; int H, V, B, P; int dtype; size_t esz;
   int Tc, Vp, tiles_v, n_chunks;
   bool bwd;
-  bool tiled;            // bf16: the work buffers dS/E, dS^T/E^T, W^T, X^T are slab-tiled (hot kernel operands)
+  bool tiled;            // bf16: the work buffers dS/E, W^T, X^T are slab-tiled (hot kernel operands)
   bool stash;            // single-pass backward (forward keeps each chunk's unnormalised probabilities)
   int n_desc, max_len;   // stash: number of chunk records, promised bound on rows per sequence
   float inv_tau;         // 1 / temperature
@@ -695,7 +695,7 @@ static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi&
 
 template <class Tune, class Epi>
 static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
-  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  const int tiles = launch_tiles((d.M + kBM - 1) / kBM, (d.N + kBN - 1) / kBN);
   const bool fast = (d.K % 128 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
                     ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
   if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
@@ -704,13 +704,13 @@ static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, con
 
 template <class Tune, class Epi>
 static void launch_gemm(const float* A, const float* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
-  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  const int tiles = launch_tiles((d.M + kBM - 1) / kBM, (d.N + kBN - 1) / kBN);
   launch_generic<float, Epi>(A, B, d, epi, tiles, s);
 }
 
 // Weight-gradient contraction of the recompute mode: bf16 reads dS (K-major A operand), f32 its stored transpose.
 static void launch_dw(const bf16_t* dS, const bf16_t*, const bf16_t* XT, const GemmDims& d, const EpiDW& epi, hipStream_t s) {
-  const int tiles = ((d.M + kBM - 1) / kBM) * ((d.N + kBN - 1) / kBN);
+  const int tiles = launch_tiles((d.M + kBM - 1) / kBM, (d.N + kBN - 1) / kBN);
   gemm_nt_bf16_kernel<EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo, true><<<tiles, 256, 0, s>>>(dS, XT, d, epi);
 }
 static void launch_dw(const float*, const float* dST, const float* XT, const GemmDims& d, const EpiDW& epi, hipStream_t s) {
@@ -794,7 +794,7 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
       transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, nullptr, nullptr, XT, p.Tc, p.Tc, p.tiled);
     }
-    {  // recompute logits, form dS and dS^T
+    {  // recompute logits, form dS (and dS^T for f32 inputs)
       GemmDims d{};
       d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
       d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
@@ -836,9 +836,9 @@ static LossOpts loss_opts(const rl_params* prm) {
 
 // Single-pass variant of forward + loss + backward (bf16 hot kernels): chunks are made of whole
 // sequences, so each chunk's loss coefficients are known as soon as its forward is; the forward
-// keeps the chunk's unnormalised probabilities E (and E^T) and the backward contractions run on
+// keeps the chunk's unnormalised probabilities E and the backward contractions run on
 // them directly: dX = diag(-c/Z) E' W and dW += E'^T diag(-c/Z) X, E' = E with the target entry
-// patched.  Three contractions per chunk instead of four; T x V is still never held, only Tc x V.
+// patched (E' is the row-major A operand of the first and the K-major A operand of the second).  Three contractions per chunk instead of four; T x V is still never held, only Tc x V.
 static void run_fused(const rl_batch* b, const rl_params* prm, int objective, const Plan& p, const Ptrs& q,
                       const rl_outputs* out, hipStream_t s) {
   typedef bf16_t T;
@@ -870,7 +870,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, p.V, p.inv_tau};
       ProfScope ps(RL_PROF_GEMM_FWD, s);
       gemm_nt_bf16_kernel<EpiFwdStash<T>, TuneLogits::kPfd, TuneLogits::kVmg, TuneLogits::kVmo>
-          <<<((p.V + kBM - 1) / kBM) * ((p.Tc + kBN - 1) / kBN), 256, 0, s>>>(W, X, d, e);
+          <<<launch_tiles((p.V + kBM - 1) / kBM, (p.Tc + kBN - 1) / kBN), 256, 0, s>>>(W, X, d, e);
     }
     {
       ProfScope ps(RL_PROF_COMBINE, s);
@@ -901,8 +901,8 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       dw.chunk = chunk; dw.dyn = 3; dw.zero_if_empty = (k == 0); dw.group_m = TuneDW::kBand; dw.a_tiled = dw.b_tiled = 1;
       EpiDW ew{out->d_weight, p.H, p.V, p.H, k > 0 ? 1 : 0};
       const int tn = (p.H + kBN - 1) / kBN;
-      const int n1 = (((p.Tc + kBM - 1) / kBM) * tn + kXcds - 1) / kXcds * kXcds;
-      const int n2 = ((p.V + kBM - 1) / kBM) * tn;
+      const int n1 = launch_tiles((p.Tc + kBM - 1) / kBM, tn);
+      const int n2 = launch_tiles((p.V + kBM - 1) / kBM, tn);
       ProfScope ps(RL_PROF_GEMM_BWD, s);
       gemm_nt_bf16_pair_kernel<EpiDX<T>, TuneDX::kPfd, TuneDX::kVmg, TuneDX::kVmo, EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo, true>
           <<<n1 + n2, 256, 0, s>>>(E, WT, dx, ex, n1, E, XT, dw, ew);
@@ -953,8 +953,9 @@ rl_status rl_profile_read(rl_profile* out) {
   return st;
 }
 
-int32_t rl_version(void) { return 106; }
+int32_t rl_version(void) { return 107; }
 int32_t rl_default_chunk_rows(void) { return kDefaultChunkRows; }
+int32_t rl_default_chunk_rows_single_pass(void) { return kDefaultChunkRowsStash; }
 
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
                                double* tflops, double* shader_mhz) {

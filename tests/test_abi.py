@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
     for n in names:
         assert hasattr(lib, n), n
     assert lib.rl_version() >= 100
-    assert lib.rl_default_chunk_rows() % 256 == 0
+    assert lib.rl_default_chunk_rows() % 256 == 0 and lib.rl_default_chunk_rows_single_pass() % 256 == 0
 
 
 def _batch(**over):
