@@ -36,9 +36,12 @@ constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 
 // Per-contraction tuning of the hot kernel, from sweeps on the 7B-shaped workload at 32768-row chunks:
 // tile-order band height (M-tiles per band), L2 prefetch distance in slabs (0 = off) and where in a
 // phase of 32 MFMAs the slab loads are issued (after MFMA kVmo, kVmo + kVmg, ...).
-struct TuneLogits { static constexpr int kBand = 8, kPfd = 4, kVmg = 5, kVmo = 3; };
-struct TuneDX     { static constexpr int kBand = 8, kPfd = 2, kVmg = 5, kVmo = 3; };
-struct TuneDW     { static constexpr int kBand = 4, kPfd = 2, kVmg = 4, kVmo = 1; };
+// Measured on the 7B shape: with the XCDs sweeping N in step the dX prefetch only costs (-4 % of dX+dW when off; its
+// band height then makes no difference between 1 and 8), dW is best with one M-tile per band (its A panel, the stored
+// probabilities, then leaves memory once for all 14 N-tiles), the logits want the prefetch (off: +4 % on the forward).
+struct TuneLogits { static constexpr int kBand = 8, kPfd = 2, kVmg = 5, kVmo = 3; };
+struct TuneDX     { static constexpr int kBand = 8, kPfd = 0, kVmg = 5, kVmo = 3; };
+struct TuneDW     { static constexpr int kBand = 1, kPfd = 2, kVmg = 4, kVmo = 1; };
 
 struct Ctrl {            // device control block at the head of the workspace
   int n_real;
