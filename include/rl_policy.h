@@ -245,6 +245,14 @@ rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float*
 rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
                                double* tflops, double* shader_mhz);
 
+/* Diagnostic (host only, nothing is launched): the workgroup -> tile map of the contraction kernels, for tests.
+ * tiles_m x tiles_n tiles, bands of group_m M-tiles, by_share = 0 (eight equal runs of the band sequence) or 1
+ * (each of the eight accelerator dies owns a share of the M-tiles).  *workgroups receives the launch size;
+ * tile[2 w] / tile[2 w + 1] (caller's array of 2 * launch size ints, or NULL to query the size only) receive
+ * the (m, n) tile of workgroup w, or (-1, -1) if it has none. */
+rl_status rl_debug_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t group_m, int32_t by_share,
+                              int32_t* workgroups, int32_t* tile);
+
 #ifdef __cplusplus
 }
 #endif

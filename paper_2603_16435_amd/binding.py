@@ -109,6 +109,8 @@ def lib() -> C.CDLL:
         L.rl_version.restype = C.c_int32
         L.rl_default_chunk_rows.restype = C.c_int32
         L.rl_default_chunk_rows_single_pass.restype = C.c_int32
+        L.rl_debug_tile_order.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.rl_debug_tile_order.restype = C.c_int
         _lib = L
     return _lib
 

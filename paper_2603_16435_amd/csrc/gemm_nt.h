@@ -112,7 +112,7 @@ __device__ inline bool resolve_dims(GemmDims& d, int& M, int& N, int& K) {
 __device__ __host__ inline int launch_tiles(int tiles_m, int tiles_n) {
   return (tiles_m + kXcds - 1) / kXcds * kXcds * tiles_n;
 }
-__device__ inline bool tile_of_block(int pid, int tiles_m, int tiles_n, int group_m, bool by_share, int& tm, int& tn) {
+__device__ __host__ inline bool tile_of_block(int pid, int tiles_m, int tiles_n, int group_m, bool by_share, int& tm, int& tn) {
   const int xcd = pid % kXcds, q = pid / kXcds;
   int t, first = 0, rows = tiles_m;                // position in the band sequence of `rows` M-tiles starting at `first`
   if (by_share) {
@@ -363,7 +363,7 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   constexpr int WM = 128, WN = 128, MB = 8, NB = 8;             // 8 x 8 blocks of 16 x 16 per wavefront
   constexpr int DSG = 2;                                        // one fragment read per DSG MFMAs
   constexpr int A_BYTES = BM * kSlabBytes, B_BYTES = BN * kSlabBytes, STAGE = A_BYTES + B_BYTES;
-  static_assert(VMO < VMG && 5 * VMG + VMO < 32, "six slab loads must fit into a phase");
+  static_assert(VMO < VMG && 5 * VMG + VMO < 32, "the six slab loads of the fullest phase must fit into its 32 MFMAs");
   static_assert(STAGE == kHotStageBytes, "stage size");
 
   int M, N, K;

@@ -147,3 +147,40 @@ def test_product_path_has_no_oracle_dependency():
             if fn.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.replace("CPU oracle", "").lower() or fn == "synth.py", (dirpath, fn)
+
+
+@pytest.mark.parametrize("by_share", [0, 1])
+def test_tile_order_visits_every_tile_once_and_keeps_dies_balanced(lib, by_share):
+    """Host logic of the workgroup -> tile map: a bijection onto the tile grid for any grid and band height,
+    every accelerator die (workgroup id % 8) gets an equal part, and with shares all dies sweep N in step."""
+    for tiles_m, tiles_n, group_m in [(1, 1, 8), (3, 5, 8), (7, 14, 1), (8, 14, 8), (20, 14, 8), (23, 3, 4), (188, 14, 8),
+                                      (594, 14, 1), (594, 160, 8), (125, 19, 16), (9, 1, 2)]:
+        n = C.c_int32(0)
+        assert lib.rl_debug_tile_order(tiles_m, tiles_n, group_m, by_share, C.byref(n), None) == 0
+        assert n.value >= tiles_m * tiles_n and n.value % 8 == 0
+        buf = (C.c_int32 * (2 * n.value))()
+        assert lib.rl_debug_tile_order(tiles_m, tiles_n, group_m, by_share, C.byref(n), buf) == 0
+        seen, per_die, seq = set(), [0] * 8, [[] for _ in range(8)]
+        for w in range(n.value):
+            tm, tn = buf[2 * w], buf[2 * w + 1]
+            if tm < 0:
+                assert tn < 0
+                continue
+            assert 0 <= tm < tiles_m and 0 <= tn < tiles_n and (tm, tn) not in seen, (tiles_m, tiles_n, group_m, w)
+            seen.add((tm, tn)); per_die[w % 8] += 1; seq[w % 8].append((tm, tn))
+        assert len(seen) == tiles_m * tiles_n
+        if by_share:
+            assert max(per_die) - min(per_die) <= tiles_n          # shares differ by at most one M-tile
+            # in step: the q-th tile of every die with a full-height share sits in the same N-tile
+            full = [s for s in seq if len(s) == max(per_die)]
+            for q in range(0, max(per_die), 7):
+                assert len({s[q][1] for s in full}) == 1
+            # an M-tile belongs to one die only
+            owner = {}
+            for die, s in enumerate(seq):
+                for tm, _ in s:
+                    assert owner.setdefault(tm, die) == die
+        else:
+            assert max(per_die) - min(per_die) <= 1
+    assert lib.rl_debug_tile_order(0, 4, 8, 0, C.byref(n), None) == 2
+    assert lib.rl_debug_tile_order(4, 4, 8, 0, None, None) == 1
