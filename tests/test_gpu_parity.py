@@ -148,6 +148,20 @@ def test_stash_mode_edges(layout):
         assert torch.equal(res.d_weight, res2.d_weight) and torch.equal(res.d_hidden, res2.d_hidden) and torch.equal(res.loss, res2.loss)
 
 
+@pytest.mark.parametrize("mode", ["recompute", "stash"])
+def test_ragged_tiles_in_every_dimension(mode):
+    # H = 384: one full and one half N-tile in dX / dW; V = 1300: five full vocabulary tiles and a ragged sixth
+    # (zero padding of the K-major operand of dW); 700 tokens in chunks of 512 rows: a full and a partly filled
+    # chunk, i.e. XCD shares of one M-tile for some dies and none for others
+    V, H = 1300, 384
+    lengths = [130, 70, 100, 50, 90, 60, 120, 80]
+    b = _edge_batch("bf16", H, V, lengths, P=2, G=4, layout="packed", seed=78)
+    for objective in ("grpo", "flow"):
+        ref = run_oracle(b, objective)
+        res = run_gpu(b, objective, chunk_rows=512, mode=mode)
+        compare_all(b, res, ref, **BF16_TOL)
+
+
 def test_stash_mode_no_tokens_and_broken_promise():
     b = _edge_batch("bf16", 128, 512, [0, 0, 0, 0], P=2, G=2)
     res = run_gpu(b, "flow", mode="stash")
