@@ -147,8 +147,8 @@ def bench_rvq_encode(a, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="7b", choices=["tiny", "small", "7b", "long", "32b"])
     ap.add_argument("--objective", default="grpo", choices=["grpo", "flow"])
     ap.add_argument("--layout", default="padded", choices=["padded", "packed"])
@@ -192,11 +192,15 @@ def main():
     binding.rl_profile_enable(True)
     binding.rl_profile_read()
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]   # on the stream the library launches on
     t0 = time.perf_counter()
-    for _ in range(a.steps):
+    marks[0].record()
+    for i in range(a.steps):
         res = plan.run(obj)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
     prof = binding.rl_profile_read()
     binding.rl_profile_enable(False)
 
@@ -244,7 +248,8 @@ def main():
     out = {
         "metric": "rollout tokens/sec, fused logprob+policy-loss fwd+bwd; % bf16 MFMA peak",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_step, "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{a.config}: P={cfg.P} G={cfg.G} len U[{cfg.len_lo},{cfg.len_hi}] H={cfg.H} V={cfg.V} "
                                f"{cfg.dtype}, {a.layout} rows R={b.R}, real tokens T={T}, objective={a.objective}"
