@@ -365,6 +365,7 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   constexpr int A_BYTES = BM * kSlabBytes, B_BYTES = BN * kSlabBytes, STAGE = A_BYTES + B_BYTES;
   static_assert(VMO < VMG && 5 * VMG + VMO < 32, "the six slab loads of the fullest phase must fit into its 32 MFMAs");
   static_assert(STAGE == kHotStageBytes, "stage size");
+  static_assert(!ATR || !Epi::kPermute, "the K-major A path loads rows in natural order");
 
   int M, N, K;
   if (!resolve_dims(d, M, N, K)) return;
