@@ -245,6 +245,28 @@ def main():
     kernels = {k: {"ms_per_step": v[0] / a.steps, "launches_per_step": v[1] / a.steps,
                    "tflops": (class_flops[k] * a.steps / (v[0] * 1e-3) / 1e12) if (k in gemms and v[0] > 0) else None}
                for k, v in prof.items()}
+    # The O(T) launch classes against the HBM roofline: algorithmic bytes per step (what the stage must read and
+    # write once, from the shapes) / event-timed duration.  They are launch-latency-bound at these sizes.
+    esz = 2 if cfg.dtype == "bf16" else 4
+    tiles_v = -(-cfg.V // 256)
+    R, Hh, Vv = b.R, cfg.H, cfg.V
+    class_bytes = {
+        # mask + ids read, three zero-filled row outputs + compaction index, compacted ids / row map written;
+        # single pass also reads each token's x row and W[y] row for the target logit
+        "prep": R * (1 + 4 + 12 + 4) + T * 8 + (T * 2 * Hh * esz if stash else 0),
+        # per-tile partials (float2 single pass, float4 recompute) in, lse / logp / entropy out
+        "combine": tiles_v * T * (8 if stash else 16) + T * 24,
+        # logp, old, ref, row map in; c_t twice out; single pass: the per-row patch and factor as well
+        "loss": T * 24 + (T * 26 if stash else 0),
+        # W -> W^T and the X chunks -> X^T (read + write), masked dX rows zeroed
+        "transpose": 2 * Vv * Hh * esz + 2 * T * Hh * esz + (R - T) * Hh * esz,
+    }
+    hbm = {}
+    for k, nbytes in class_bytes.items():
+        ms = prof[k][0] / a.steps
+        if ms > 0:
+            gbps = nbytes / (ms * 1e-3) / 1e9
+            hbm[k] = {"ms_per_step": ms, "algorithmic_bytes_per_step": nbytes, "gbps": gbps, "frac_of_8TBps": gbps / 8000.0}
     out = {
         "metric": "rollout tokens/sec, fused logprob+policy-loss fwd+bwd; % bf16 MFMA peak",
         "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -271,6 +293,7 @@ def main():
                                "sustained_1s": {"tflops": peak_sustained[0], "shader_mhz": peak_sustained[1]},
                                "roofline_frac_of_sustained": achieved / peak_sustained[0] if peak_sustained[0] > 0 else None},
         "kernels": kernels,
+        "hbm_bound_classes": hbm,
         "loss": loss,
     }
     if not a.no_cpu_baseline:

@@ -294,23 +294,25 @@ __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, con
 }
 
 // Per-tile-row partial sums (s, u) of a chunk -> lse, logp, entropy and Z_t = sum_v exp(z - ref_t).
-// A workgroup handles 64 rows x 4 slices of the tile range, merged through LDS in a fixed order.
-__global__ void lse_sum_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c, const float* ref_l2e,
+// A workgroup handles 64 rows x 16 slices of the tile range (1024 threads: the sums are chains of dependent f64 adds,
+// so it takes many short chains to keep the memory system busy), merged through LDS in a fixed order.
+constexpr int kSumSlices = 16;
+__global__ __launch_bounds__(64 * kSumSlices) void lse_sum_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c, const float* ref_l2e,
                                const int32_t* row_map, const ChunkDesc* desc,
                                float* lse_c, float* logp_c, float* zsum_c, float* lse_out, float* logp_out, float* ent_out) {
-  __shared__ double ss[4][64], su[4][64];
+  __shared__ double ss[kSumSlices][64], su[kSumSlices][64];
   const int left = desc->rows, chunk_start = desc->row_start;
   if ((int)blockIdx.x * 64 >= left) return;
   const int col = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + col;
   double s = 0.0, u = 0.0;
   if (n < left)
-    for (int t = slice; t < tiles_v; t += 4) { const float2 v = part[(int64_t)t * ldp + n]; s += (double)v.x; u += (double)v.y; }
+    for (int t = slice; t < tiles_v; t += kSumSlices) { const float2 v = part[(int64_t)t * ldp + n]; s += (double)v.x; u += (double)v.y; }
   ss[slice][col] = s; su[slice][col] = u;
   __syncthreads();
   if (slice == 0 && n < left) {
-    const double S = ss[0][col] + ss[1][col] + ss[2][col] + ss[3][col];
-    const double U = su[0][col] + su[1][col] + su[2][col] + su[3][col];
+    double S = 0.0, U = 0.0;
+    for (int k = 0; k < kSumSlices; ++k) { S += ss[k][col]; U += su[k][col]; }
     const int g = chunk_start + n;
     const double lse_d = (double)ref_l2e[g] * 0.6931471805599453 + log(S);
     const float lse = (float)lse_d;
@@ -566,6 +568,72 @@ __global__ void transpose_kernel(const T* src, int64_t ld_src, int rows, int col
   }
 }
 
+// The same for bf16 with 16-byte accesses on both sides (cols % 8 == 0, 16-byte aligned rows; rows_padded % 8 == 0, tiled
+// destination): a thread loads two 16-byte pieces of source rows and stores two 16-byte pieces of destination rows, each
+// gathered from eight consecutive source rows of one column in LDS (row stride 33 dwords: the gather is conflict-free).
+__global__ __launch_bounds__(256)
+void transpose_bf16_kernel(const bf16_t* src, int64_t ld_src, int rows, int cols, const int32_t* row_idx,
+                           const Ctrl* ctrl, int chunk_start, int dyn_rows, const ChunkDesc* desc, const float* row_scale,
+                           bf16_t* dst, int64_t ld_dst, int rows_padded) {
+  __shared__ unsigned tile[64][33];
+  int rv = rows;
+  if (dyn_rows) {
+    int left;
+    if (desc) { chunk_start = desc->row_start; left = desc->rows; } else left = ctrl->n_real - chunk_start;
+    if (left <= 0) return;
+    rv = left < rows ? left : rows;
+  }
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  if (dyn_rows && r0 >= ((rv + 255) & ~255)) return;
+  const int ch = threadIdx.x & 7, k0 = threadIdx.x >> 3;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int k = k0 + 32 * p, r = r0 + k, c = c0 + 8 * ch;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < rv && c < cols) {
+      const int64_t sr = row_idx ? (int64_t)row_idx[chunk_start + r] : (int64_t)r;
+      v = *reinterpret_cast<const uint4*>(src + sr * ld_src + c);
+      if (row_scale) {
+        const float f = row_scale[r];
+        bf16x8 e = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) e[i] = (bf16_t)((float)e[i] * f);
+        v = __builtin_bit_cast(uint4, e);
+      }
+    }
+    tile[k][4 * ch] = v.x; tile[k][4 * ch + 1] = v.y; tile[k][4 * ch + 2] = v.z; tile[k][4 * ch + 3] = v.w;
+  }
+  __syncthreads();
+  const unsigned short* t16 = reinterpret_cast<const unsigned short*>(&tile[0][0]);
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int k = k0 + 32 * p, c = c0 + k, r = r0 + 8 * ch;
+    if (c < cols && r < rows_padded) {
+      unsigned w[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        w[i] = (unsigned)t16[(8 * ch + 2 * i) * 66 + k] | ((unsigned)t16[(8 * ch + 2 * i + 1) * 66 + k] << 16);
+      *reinterpret_cast<uint4*>(dst + tiled_index(c, r, ld_dst)) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
+// Host side: the 16-byte kernel where its conditions hold (always, for the library's own bf16 buffers and 16-byte aligned inputs).
+template <class T>
+static void launch_transpose(dim3 grid, hipStream_t s, const T* src, int64_t ld_src, int rows, int cols, const int32_t* row_idx,
+                             const Ctrl* ctrl, int chunk_start, int dyn_rows, const ChunkDesc* desc, const float* row_scale,
+                             T* dst, int64_t ld_dst, int rows_padded, bool dst_tiled) {
+  if constexpr (sizeof(T) == 2) {
+    if (dst_tiled && cols % 8 == 0 && ld_src % 8 == 0 && rows_padded % 8 == 0 && reinterpret_cast<uintptr_t>(src) % 16 == 0) {
+      transpose_bf16_kernel<<<grid, 256, 0, s>>>(src, ld_src, rows, cols, row_idx, ctrl, chunk_start, dyn_rows, desc, row_scale,
+                                                 dst, ld_dst, rows_padded);
+      return;
+    }
+  }
+  transpose_kernel<T><<<grid, 256, 0, s>>>(src, ld_src, rows, cols, row_idx, ctrl, chunk_start, dyn_rows, desc, row_scale,
+                                           dst, ld_dst, rows_padded, dst_tiled);
+}
+
 // ------------------------------------------------------------------ MFMA ceiling probe (benchmark aid)
 __global__ __launch_bounds__(256) void mfma_peak_kernel(float* out, int iters, long long* clk) {
   // the hot kernel's own instruction and register blocking: 8 x 8 blocks of v_mfma_f32_16x16x32_bf16
@@ -787,14 +855,14 @@ static void run_backward(const rl_batch* b, const Plan& p, const Ptrs& q, void* 
   {
     ProfScope ps(RL_PROF_TRANSPOSE, s);
     dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
-    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp, p.tiled);
+    launch_transpose<T>(g, s, W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp, p.tiled);
   }
   for (int ch = 0; ch < p.n_chunks; ++ch) {
     const int c0 = ch * p.Tc;
     {  // X^T chunk [H][Tc], gathered through row_map, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
-      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, nullptr, nullptr, XT, p.Tc, p.Tc, p.tiled);
+      launch_transpose<T>(g, s, X, p.H, p.Tc, p.H, q.row_map, q.ctrl, c0, 1, nullptr, nullptr, XT, p.Tc, p.Tc, p.tiled);
     }
     {  // recompute logits, form dS (and dS^T for f32 inputs)
       GemmDims d{};
@@ -854,7 +922,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     const int rows_per_block = 4;
     zero_masked_rows_kernel<T><<<(unsigned)((p.R + rows_per_block - 1) / rows_per_block), 256, 0, s>>>(q.cpos, dX, p.R, p.H);
     dim3 g((p.Vp + 63) / 64, (p.H + 63) / 64);
-    transpose_kernel<T><<<g, 256, 0, s>>>(W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp, p.tiled);
+    launch_transpose<T>(g, s, W, p.H, p.V, p.H, nullptr, q.ctrl, 0, 0, nullptr, nullptr, WT, p.Vp, p.Vp, p.tiled);
   }
   {
     ProfScope ps(RL_PROF_PREP, s);
@@ -876,7 +944,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     }
     {
       ProfScope ps(RL_PROF_COMBINE, s);
-      lse_sum_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(part, p.Tc, p.tiles_v, q.zy, q.ref, q.row_map, dk, q.lse_c, q.logp_c, q.zsum,
+      lse_sum_kernel<<<(p.Tc + 63) / 64, 64 * kSumSlices, 0, s>>>(part, p.Tc, p.tiles_v, q.zy, q.ref, q.row_map, dk, q.lse_c, q.logp_c, q.zsum,
                                                       out->lse, out->logprob, out->entropy);
     }
     {
@@ -889,7 +957,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     {  // X^T chunk scaled by -c/Z, zero beyond the valid rows
       ProfScope ps(RL_PROF_TRANSPOSE, s);
       dim3 g((p.Tc + 63) / 64, (p.H + 63) / 64);
-      transpose_kernel<T><<<g, 256, 0, s>>>(X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc, true);
+      launch_transpose<T>(g, s, X, p.H, p.Tc, p.H, q.row_map, q.ctrl, 0, 1, dk, q.scale, XT, p.Tc, p.Tc, true);
     }
     {  // dX = diag(-c/Z) E' W  (A = E' [Tc][Vp], B = W^T [H][Vp]) and dW (+)= E'^T (diag(-c/Z) X)  (A = E'^T, read out
        // of E' itself as a K-major operand; B = scaled X^T [H][Tc]) in one launch: dX alone has too few (long) tiles
