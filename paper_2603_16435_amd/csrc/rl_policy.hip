@@ -802,7 +802,8 @@ static Ptrs carve(void* ws, const Plan& p) {
   q.zy = (float*)(w + p.off_zy); q.lse_c = (float*)(w + p.off_lse_c); q.logp_c = (float*)(w + p.off_logp_c);
   q.c_c = (float*)(w + p.off_c_c); q.adv = (float*)(w + p.off_adv); q.seq_loss = (float*)(w + p.off_seq_loss);
   q.gterm = (float*)(w + p.off_gterm); q.part = (float4*)(w + p.off_part);
-  q.wt = w + p.off_wt; q.xt = w + p.off_xt; q.ds = w + p.off_ds; q.dst = w + p.off_dst;
+  q.wt = w + p.off_wt; q.xt = w + p.off_xt; q.ds = w + p.off_ds;
+  q.dst = p.off_dst ? w + p.off_dst : nullptr;          // f32 inputs only
   q.desc = (ChunkDesc*)(w + p.off_desc); q.ref = (float*)(w + p.off_ref); q.zsum = (float*)(w + p.off_zsum);
   q.scale = (float*)(w + p.off_scale);
   return q;
