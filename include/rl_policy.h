@@ -14,8 +14,10 @@
  *            delta_i = logZ_g(i) + (1/|y_i|) sum_t (logp_t - ref_t) - beta A_i,
  *            w_i = clip(exp(sum_t (logp_t - old_t)), 1-e, 1+e) held constant
  * and the backward pass  c_t = dloss/dlogp_t,  dS[t,v] = c_t (1[v=y_t] - softmax(z_t)[v]),
- * dX = dS W, dW = dS^T X, with the logits recomputed tile by tile (T x V is never stored;
- * only a chunk of dS in the input precision is staged between the three contractions).
+ * dX = dS W, dW = dS^T X.  T x V is never stored: either the logits are recomputed tile by
+ * tile and a chunk of dS in the input precision is staged between the contractions, or the
+ * forward keeps a chunk's unnormalised probabilities and the backward is contracted from
+ * those (rl_backward_mode).  Optionally the policy is softmax(W x_t / temperature).
  *
  * Conventions
  *  - Every pointer in rl_batch / rl_outputs and the workspace is a DEVICE pointer owned by
