@@ -4,7 +4,9 @@
 //
 // Every contraction of the path is brought into this form (K contiguous in both operands)
 // so that one MFMA main loop serves the forward logits, the recomputed logits, dX and dW;
-// what differs is the epilogue functor that consumes the accumulators in registers.
+// what differs is the epilogue functor that consumes the accumulators in registers.  One
+// exception: the hot kernel can also take its A operand K-major (the stored array is A^T, rows = k),
+// read through transposing LDS loads; dW uses that to contract dS^T X out of dS itself.
 //
 // Two kernels share tile order, LDS layout and epilogues:
 //  * gemm_nt_bf16_kernel  - the hot one (bf16, K % 128 == 0).  256x256 tile, four wavefronts of
@@ -17,8 +19,8 @@
 //    and the last phase of a slab runs after the workgroup barrier so that it hides the first
 //    fragment reads of the next slab.  The MFMAs are inline asm and every one is fenced with
 //    sched_barrier, so the interleaving in the source is the interleaving issued.  A light
-//    software prefetch (one 4-byte load per 128-byte line, a few slabs ahead, shared between the
-//    workgroups of an XCD) pulls the next panels into that XCD's L2.
+//    software prefetch (one 4-byte load per 128-byte line, two slabs ahead, shared between the
+//    workgroups of an XCD; off for dX) pulls the next panels into that XCD's L2.
 //  * gemm_nt_kernel       - generic fallback (f32 inputs, or K not a multiple of 128): eight
 //    wavefronts of 128x64, 32x32 MFMA blocks, register-staged loads with a K-tail predicate.
 //
