@@ -754,12 +754,10 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
 // inputs, ragged K) takes the generic kernel.
 template <class T, class Epi>
 static void launch_generic(const T* A, const T* B, const GemmDims& d, const Epi& epi, int tiles, hipStream_t s) {
-  static bool attr_set = false;
   auto kern = gemm_nt_kernel<T, Epi, kBM, kBN, kWavesM, kWavesN>;
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmSmem);
-    attr_set = true;
-  }
+  // 128 KiB of dynamic LDS needs the opt-in on every device the caller may be on: set on each launch (a host-side table
+  // update, no device work) rather than remembered in a flag that is neither per device nor thread-safe
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kGemmSmem);
   kern<<<tiles, kGemmThreads, kGemmSmem, s>>>(A, B, d, epi);
 }
 
