@@ -334,7 +334,9 @@ __device__ __attribute__((always_inline)) inline void mfma16(floatx4& acc, const
 __device__ __attribute__((always_inline)) inline void mfma_drain() { asm volatile("s_nop 15\n\ts_nop 15" ::: "memory"); }
 
 // PFD: L2 prefetch distance in slabs (0 = none).  VMG / VMO: inside a phase of 32 MFMAs the slab loads
-// are issued after MFMA number VMO, VMO + VMG, VMO + 2 VMG, ...
+// are issued after MFMA number VMO, VMO + VMG, VMO + 2 VMG, ...  LDA / LDB: how many of a slab's 16 loads go
+// into the phase after the barrier and into the first phase of the next slab (the rest into its second phase);
+// the earlier they go, the longer they have to land before the next barrier.
 constexpr int kHotStageBytes = (256 + 256) * kSlabBytes;      // one LDS stage of the hot kernel: a slab of A and of B
 
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes, the four 16-bit values that lane
@@ -358,14 +360,17 @@ __device__ __attribute__((always_inline)) inline u32x2_t lds_read_tr16(const uns
 // 64 k-rows of 256 m (512 bytes a row, 32-byte pieces XOR-swizzled by a function of the row such that the eight
 // rows a half-wavefront's transposing read touches fall into different banks) and its fragments come from two
 // transposing reads each.
-template <class Epi, int PFD, int VMG, int VMO, bool ATR = false>
+template <class Epi, int PFD, int VMG, int VMO, bool ATR = false, int LDA = 6, int LDB = 5>
 __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d,
                                                                         const Epi& epi, int pid, unsigned char* stage0, unsigned char* stage1) {
   constexpr int BM = 256, BN = 256, BK = 64, WAVES_M = 2, WAVES_N = 2;
   constexpr int WM = 128, WN = 128, MB = 8, NB = 8;             // 8 x 8 blocks of 16 x 16 per wavefront
   constexpr int DSG = 2;                                        // one fragment read per DSG MFMAs
   constexpr int A_BYTES = BM * kSlabBytes, B_BYTES = BN * kSlabBytes, STAGE = A_BYTES + B_BYTES;
-  static_assert(VMO < VMG && 5 * VMG + VMO < 32, "the six slab loads of the fullest phase must fit into its 32 MFMAs");
+  constexpr int LDC = 16 - LDA - LDB;
+  constexpr int LDMAX = LDA > LDB ? (LDA > LDC ? LDA : LDC) : (LDB > LDC ? LDB : LDC);
+  static_assert(LDA >= 0 && LDB >= 0 && LDC >= 0 && VMO < VMG && (LDMAX - 1) * VMG + VMO < 32,
+                "the slab loads of the fullest phase must fit into its 32 MFMAs");
   static_assert(STAGE == kHotStageBytes, "stage size");
   static_assert(!ATR || !Epi::kPermute, "the K-major A path loads rows in natural order");
 
@@ -518,16 +523,16 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   };
 
   // Slab kt sits in `cur`.  On entry fa[0] / fb[0] hold its k-step 0 (A all, B blocks 0..3) and loads
-  // 0..5 of slab kt+1 are in flight towards `nxt`.  The last phase runs from registers after the
+  // 0..LDA-1 of slab kt+1 are in flight towards `nxt`.  The last phase runs from registers after the
   // workgroup barrier, so it covers the first fragment reads of slab kt+1 and the first loads of kt+2.
   auto slab = [&](unsigned char* cur, unsigned char* nxt, int kt, unsigned& pfslot) __attribute__((always_inline)) {
     prefetch(pfslot, kt);
-    phase(0, 0, 0, 4, cur, 0, kof(kt + 1), nxt, 6, 5);
-    phase(0, 1, 1, 12, cur, 1, kof(kt + 1), nxt, 11, 5);
+    phase(0, 0, 0, 4, cur, 0, kof(kt + 1), nxt, LDA, LDB);
+    phase(0, 1, 1, 12, cur, 1, kof(kt + 1), nxt, LDA + LDB, LDC);
     phase(1, 0, 0, 4, cur, 1, 0, nxt, 0, 0);
     __builtin_amdgcn_s_waitcnt(0x0070);     // vmcnt(0) lgkmcnt(0): own loads have landed, own fragment reads are done
     __syncthreads();                        // ... and so have everybody else's: `nxt` is complete, `cur` is free
-    phase(1, 1, 1, 12, nxt, 0, kof(kt + 2), cur, 0, 6);
+    phase(1, 1, 1, 12, nxt, 0, kof(kt + 2), cur, 0, LDA);
   };
 
   if (nk > 0) {
@@ -536,7 +541,7 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
     __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0)
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 6; ++j) issue1(kof(1), stage1, j);
+    for (int j = 0; j < LDA; ++j) issue1(kof(1), stage1, j);
     {
       const int slot = (fq ^ swz) << 4;
 #pragma unroll
@@ -560,26 +565,28 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   if (PFD > 0 && (pf_sink ^ pf0 ^ pf1) == 0x9E3779B9u && K < 0) epi.keep_alive();   // never true: keeps the prefetch loads
 }
 
-template <class Epi, int PFD, int VMG, int VMO, bool ATR = false>
+template <class Epi, class Tune, bool ATR = false>
 __global__ __launch_bounds__(256)
 void gemm_nt_bf16_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, Epi epi) {
   __shared__ __attribute__((aligned(1024))) unsigned char stage0[kHotStageBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char stage1[kHotStageBytes];
-  gemm_nt_bf16_tile<Epi, PFD, VMG, VMO, ATR>(A, B, d, epi, blockIdx.x, stage0, stage1);
+  gemm_nt_bf16_tile<Epi, Tune::kPfd, Tune::kVmg, Tune::kVmo, ATR, Tune::kLdA, Tune::kLdB>(A, B, d, epi, blockIdx.x, stage0, stage1);
 }
 
 // Two independent contractions in one launch: workgroups [0, n1) work on the first, the rest on the
 // second.  Used where one of them alone has too few tiles to fill the last round of the 256 CUs: the
 // other's workgroups then fill the tail.  n1 = launch_tiles() of the first (a multiple of the XCD count).
 // ATR2: the second contraction's A operand is given K-major (see gemm_nt_bf16_tile).
-template <class Epi1, int PFD1, int VMG1, int VMO1, class Epi2, int PFD2, int VMG2, int VMO2, bool ATR2 = false>
+template <class Epi1, class Tune1, class Epi2, class Tune2, bool ATR2 = false>
 __global__ __launch_bounds__(256)
 void gemm_nt_bf16_pair_kernel(const bf16_t* __restrict__ A1, const bf16_t* __restrict__ B1, GemmDims d1, Epi1 epi1, int n1,
                               const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2, GemmDims d2, Epi2 epi2) {
   __shared__ __attribute__((aligned(1024))) unsigned char stage0[kHotStageBytes];
   __shared__ __attribute__((aligned(1024))) unsigned char stage1[kHotStageBytes];
-  if ((int)blockIdx.x < n1) gemm_nt_bf16_tile<Epi1, PFD1, VMG1, VMO1>(A1, B1, d1, epi1, blockIdx.x, stage0, stage1);
-  else gemm_nt_bf16_tile<Epi2, PFD2, VMG2, VMO2, ATR2>(A2, B2, d2, epi2, (int)blockIdx.x - n1, stage0, stage1);
+  if ((int)blockIdx.x < n1)
+    gemm_nt_bf16_tile<Epi1, Tune1::kPfd, Tune1::kVmg, Tune1::kVmo, false, Tune1::kLdA, Tune1::kLdB>(A1, B1, d1, epi1, blockIdx.x, stage0, stage1);
+  else
+    gemm_nt_bf16_tile<Epi2, Tune2::kPfd, Tune2::kVmg, Tune2::kVmo, ATR2, Tune2::kLdA, Tune2::kLdB>(A2, B2, d2, epi2, (int)blockIdx.x - n1, stage0, stage1);
 }
 
 }  // namespace rlk

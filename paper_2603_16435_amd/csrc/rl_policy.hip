@@ -33,14 +33,18 @@ constexpr int kBM = 256, kBN = 256, kWavesM = 2, kWavesN = 4;
 constexpr int kGemmThreads = kWavesM * kWavesN * 64;
 constexpr int kGemmSmem = 2 * (kBM + kBN) * kSlabBytes;   // 128 KiB of the 160 KiB per CU
 // Per-contraction tuning of the hot kernel, from sweeps on the 7B-shaped workload:
-// tile-order band height (M-tiles per band), L2 prefetch distance in slabs (0 = off) and where in a
-// phase of 32 MFMAs the slab loads are issued (after MFMA kVmo, kVmo + kVmg, ...).
+// tile-order band height (M-tiles per band), L2 prefetch distance in slabs (0 = off), where in a
+// phase of 32 MFMAs the slab loads are issued (after MFMA kVmo, kVmo + kVmg, ...) and how many of a slab's 16 loads
+// go into the phase after the barrier / the next phase (kLdA / kLdB; the rest into the phase after that).
 // Measured on the 7B shape: with the XCDs sweeping N in step the dX prefetch only costs (-4 % of dX+dW when off; its
 // band height then makes no difference between 1 and 8), dW is best with one M-tile per band (its A panel, the stored
 // probabilities, then leaves memory once for all 14 N-tiles), the logits want the prefetch (off: +4 % on the forward).
-struct TuneLogits { static constexpr int kBand = 8, kPfd = 2, kVmg = 5, kVmo = 3; };
-struct TuneDX     { static constexpr int kBand = 8, kPfd = 0, kVmg = 5, kVmo = 3; };
-struct TuneDW     { static constexpr int kBand = 1, kPfd = 2, kVmg = 4, kVmo = 1; };
+// dX, whose operands both stream from memory, waits 17 % of its loop time for its slab loads with the 6/5/5 placement and
+// 5 % with 8/8/0 (all loads at least two phases before the barrier); at the power limit that is worth 0.8 % of dX+dW.
+// The other two lose with 8/8/0.
+struct TuneLogits { static constexpr int kBand = 8, kPfd = 2, kVmg = 5, kVmo = 3, kLdA = 6, kLdB = 5; };
+struct TuneDX     { static constexpr int kBand = 8, kPfd = 0, kVmg = 4, kVmo = 1, kLdA = 8, kLdB = 8; };
+struct TuneDW     { static constexpr int kBand = 1, kPfd = 2, kVmg = 4, kVmo = 1, kLdA = 6, kLdB = 5; };
 
 struct Ctrl {            // device control block at the head of the workspace
   int n_real;
@@ -767,7 +771,7 @@ static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, con
   const bool fast = (d.K % 128 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
                     ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
   if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
-  gemm_nt_bf16_kernel<Epi, Tune::kPfd, Tune::kVmg, Tune::kVmo><<<tiles, 256, 0, s>>>(A, B, d, epi);
+  gemm_nt_bf16_kernel<Epi, Tune><<<tiles, 256, 0, s>>>(A, B, d, epi);
 }
 
 template <class Tune, class Epi>
@@ -779,7 +783,7 @@ static void launch_gemm(const float* A, const float* B, const GemmDims& d, const
 // Weight-gradient contraction of the recompute mode: bf16 reads dS (K-major A operand), f32 its stored transpose.
 static void launch_dw(const bf16_t* dS, const bf16_t*, const bf16_t* XT, const GemmDims& d, const EpiDW& epi, hipStream_t s) {
   const int tiles = launch_tiles((d.M + kBM - 1) / kBM, (d.N + kBN - 1) / kBN);
-  gemm_nt_bf16_kernel<EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo, true><<<tiles, 256, 0, s>>>(dS, XT, d, epi);
+  gemm_nt_bf16_kernel<EpiDW, TuneDW, true><<<tiles, 256, 0, s>>>(dS, XT, d, epi);
 }
 static void launch_dw(const float*, const float* dST, const float* XT, const GemmDims& d, const EpiDW& epi, hipStream_t s) {
   launch_gemm<TuneDW>(dST, XT, d, epi, s);
@@ -938,7 +942,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       d.b_rows = q.row_map; d.chunk = chunk; d.dyn = 2; d.group_m = TuneLogits::kBand;
       EpiFwdStash<T> e{q.ref, part, p.Tc, E, p.Vp, p.V, p.inv_tau};
       ProfScope ps(RL_PROF_GEMM_FWD, s);
-      gemm_nt_bf16_kernel<EpiFwdStash<T>, TuneLogits::kPfd, TuneLogits::kVmg, TuneLogits::kVmo>
+      gemm_nt_bf16_kernel<EpiFwdStash<T>, TuneLogits>
           <<<launch_tiles((p.V + kBM - 1) / kBM, (p.Tc + kBN - 1) / kBN), 256, 0, s>>>(W, X, d, e);
     }
     {
@@ -973,7 +977,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
       const int n1 = launch_tiles((p.Tc + kBM - 1) / kBM, tn);
       const int n2 = launch_tiles((p.V + kBM - 1) / kBM, tn);
       ProfScope ps(RL_PROF_GEMM_BWD, s);
-      gemm_nt_bf16_pair_kernel<EpiDX<T>, TuneDX::kPfd, TuneDX::kVmg, TuneDX::kVmo, EpiDW, TuneDW::kPfd, TuneDW::kVmg, TuneDW::kVmo, true>
+      gemm_nt_bf16_pair_kernel<EpiDX<T>, TuneDX, EpiDW, TuneDW, true>
           <<<n1 + n2, 256, 0, s>>>(E, WT, dx, ex, n1, E, XT, dw, ew);
     }
   }
