@@ -107,6 +107,98 @@ def segment_lengths(mask, cu_seqlens):
 
 
 # --------------------------------------------------------------------------
+# integer work: which rows count, in which order, and how the groups are filled
+# --------------------------------------------------------------------------
+def valid_sequences(cu_seqlens, R):
+    """Which sequences have a usable row range (boolean [B]).
+
+    The problem statement takes well-formed offsets as given (cu[0] = 0, non-decreasing, cu[B] = R).
+    Reading for offsets that are not: sequence i keeps its rows iff 0 <= cu[i] <= cu[i+1] <= R and
+    cu[i] is not below any earlier offset cu[0..i]; otherwise it is treated as empty.  Kept ranges are
+    then pairwise disjoint and in increasing order, whatever the offsets were."""
+    cu = np.asarray(cu_seqlens).astype(np.int64)
+    B = cu.size - 1
+    ok = np.zeros(B, dtype=bool)
+    highest = None
+    for i in range(B):
+        highest = cu[i] if highest is None else max(highest, cu[i])
+        ok[i] = (0 <= cu[i] <= cu[i + 1] <= R) and cu[i] >= highest
+    return ok
+
+
+def compact_rows(mask, token_ids, cu_seqlens, V, group_idx=None, P=None):
+    """The rows that count, in the order the path walks them.
+
+    A row counts iff it lies in the range of a usable sequence (valid_sequences; with group_idx given the
+    sequence's prompt index must also lie in [0, P)), its mask is non-zero and its token id lies in [0, V).
+    Returns dict(row_map[T] = original row of the k-th counting row (sequence by sequence, rows ascending),
+    seq_len[B], n_bad_token, n_bad_seq, n_bad_group); rows outside every sequence never count."""
+    m = np.asarray(mask)
+    ids = np.asarray(token_ids).astype(np.int64)
+    cu = np.asarray(cu_seqlens).astype(np.int64)
+    R = m.shape[0]
+    B = cu.size - 1
+    ok = valid_sequences(cu, R)
+    grp_ok = np.ones(B, dtype=bool)
+    if group_idx is not None:
+        g = np.asarray(group_idx).astype(np.int64)
+        grp_ok = (g >= 0) & (g < P)
+    row_map = []
+    seq_len = np.zeros(B, dtype=np.int64)
+    n_bad_token = 0
+    for i in range(B):
+        if not (ok[i] and grp_ok[i]):
+            continue
+        for r in range(cu[i], cu[i + 1]):
+            if m[r] == 0:
+                continue
+            if 0 <= ids[r] < V:
+                row_map.append(r)
+                seq_len[i] += 1
+            else:
+                n_bad_token += 1
+    return dict(row_map=np.array(row_map, dtype=np.int64), seq_len=seq_len, n_bad_token=n_bad_token,
+                n_bad_seq=int((~ok).sum()), n_bad_group=int((~grp_ok).sum()))
+
+
+def group_count(group_idx, P):
+    """Number of sequences that name each prompt (indices outside [0, P) belong to none)."""
+    g = np.asarray(group_idx).astype(np.int64)
+    return np.array([int((g == p).sum()) for p in range(P)], dtype=np.int64)
+
+
+def target_logit(hidden, weight, token_ids, mask, temperature=1.0):
+    """z_t[y_t] = W[y_t] . x_t / temperature for every counting row (0 on masked rows): the gather written
+    as the one dot product it is, without forming the other logits."""
+    X = widen(hidden); W = widen(weight)
+    ids = np.asarray(token_ids).astype(np.int64)
+    m = np.asarray(mask).astype(bool)
+    zy = np.zeros(X.shape[0])
+    for t in np.nonzero(m)[0]:
+        zy[t] = float(np.dot(W[ids[t]], X[t])) / temperature
+    return zy
+
+
+def weight_grad_rows(hidden, weight_rows, vocab_rows, token_ids, mask, lse, c, temperature=1.0):
+    """Rows `vocab_rows` of dW = dS^T X, straight from the definition, for the given rows of the batch:
+         dS[t, v] = c_t (1[v = y_t] - exp(W[v] . x_t / temperature - lse_t)) / temperature,
+         dW[v, :] = sum_t m_t dS[t, v] x_t.
+    weight_rows = W[vocab_rows] ([n, H]).  dW is a plain sum over rows, so a large batch may be fed in
+    row blocks and the results added.  lse is taken as given (it is an input here, like c)."""
+    X = widen(hidden); Wr = widen(weight_rows)
+    vs = np.asarray(vocab_rows).astype(np.int64)
+    ids = np.asarray(token_ids).astype(np.int64)
+    m = np.asarray(mask).astype(bool)
+    lse = np.asarray(lse, dtype=np.float64); c = np.asarray(c, dtype=np.float64)
+    rows = np.nonzero(m)[0]
+    Z = X[rows] @ Wr.T / temperature                       # [n_rows, n] logits of the sampled vocabulary entries
+    dS = -np.exp(Z - lse[rows][:, None])
+    dS += (ids[rows][:, None] == vs[None, :])
+    dS *= (c[rows] / temperature)[:, None]
+    return dS.T @ X[rows]
+
+
+# --------------------------------------------------------------------------
 # group-relative advantage
 # --------------------------------------------------------------------------
 def group_advantage(rewards, group_idx, P, adv_eps=1e-6, ddof=0):

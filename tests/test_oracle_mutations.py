@@ -49,6 +49,14 @@ MUTANTS = [
     ("temperature: backward probabilities untempered", "dS = -np.exp(Z / temperature - lse[rows][:, None])", "dS = -np.exp(Z - lse[rows][:, None])"),
     ("temperature: chain factor dropped in the backward", "dS *= c[rows][:, None] / temperature", "dS *= c[rows][:, None]"),
     ("variant: flow upper bound", "hi_b = np.log(1.0 + (clip_eps if clip_eps_high is None else clip_eps_high))", "hi_b = np.log(1.0 + clip_eps)"),
+    ("compaction: out-of-range ids counted", "            if 0 <= ids[r] < V:\n", "            if True:\n"),
+    ("compaction: masked rows counted", "            if m[r] == 0:\n                continue\n", ""),
+    ("compaction: overlapping ranges kept", "ok[i] = (0 <= cu[i] <= cu[i + 1] <= R) and cu[i] >= highest", "ok[i] = (0 <= cu[i] <= cu[i + 1] <= R)"),
+    ("compaction: bad prompt index keeps its rows", "        if not (ok[i] and grp_ok[i]):", "        if not ok[i]:"),
+    ("target logit: wrong row of W", "zy[t] = float(np.dot(W[ids[t]], X[t])) / temperature", "zy[t] = float(np.dot(W[(ids[t] + 1) % W.shape[0]], X[t])) / temperature"),
+    ("dW rows: one-hot dropped", "    dS += (ids[rows][:, None] == vs[None, :])\n", ""),
+    ("dW rows: chain factor of the temperature dropped", "    dS *= (c[rows] / temperature)[:, None]", "    dS *= c[rows][:, None]"),
+    ("dW rows: masked rows leak", "    rows = np.nonzero(m)[0]\n    Z = X[rows] @ Wr.T", "    rows = np.arange(m.size)\n    Z = X[rows] @ Wr.T"),
 ]
 
 PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]

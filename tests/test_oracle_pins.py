@@ -622,3 +622,115 @@ def test_temperature_whole_path_by_finite_differences(objective):
     assert fold["loss"] == pytest.approx(base["loss"], abs=1e-13)
     np.testing.assert_allclose(fold["d_hidden"], base["d_hidden"], atol=1e-13)
     np.testing.assert_allclose(fold["d_weight"] / tau, base["d_weight"], atol=1e-13)
+
+
+# ---------------------------------------------------------------------------
+# integer work: usable sequences, row compaction, group sizes
+# ---------------------------------------------------------------------------
+def test_valid_sequences_hand_cases():
+    # well-formed offsets: every sequence usable (empty ones included)
+    assert orc.valid_sequences([0, 3, 3, 7, 10], 10).tolist() == [True, True, True, True]
+    # the range of the last sequence runs past the rows
+    assert orc.valid_sequences([0, 3, 12], 10).tolist() == [True, False]
+    # a negative start
+    assert orc.valid_sequences([-2, 3, 10], 10).tolist() == [False, True]
+    # alternating {0, R, 0, R}: only the first range may be kept, or rows would count twice
+    assert orc.valid_sequences([0, 10, 0, 10], 10).tolist() == [True, False, False]
+    # decreasing, then increasing again below an earlier offset: [5, 20) overlaps [0, 10)
+    assert orc.valid_sequences([0, 10, 5, 20], 20).tolist() == [True, False, False]
+    # decreasing, then increasing from above every earlier offset: usable again
+    assert orc.valid_sequences([0, 10, 5, 12, 20], 20).tolist() == [True, False, False, True]
+
+
+def test_valid_sequences_kept_ranges_never_overlap():
+    rng = np.random.default_rng(50)
+    for _ in range(200):
+        R = int(rng.integers(1, 30))
+        cu = rng.integers(-3, R + 4, size=int(rng.integers(2, 9)))
+        ok = orc.valid_sequences(cu, R)
+        hits = np.zeros(R, dtype=np.int64)
+        for i in np.nonzero(ok)[0]:
+            assert 0 <= cu[i] <= cu[i + 1] <= R
+            hits[cu[i]:cu[i + 1]] += 1
+        assert hits.max(initial=0) <= 1
+        # a sorted chain inside [0, R] keeps everything
+        s = np.sort(np.clip(cu, 0, R))
+        assert orc.valid_sequences(s, R).all()
+
+
+def test_compact_rows_hand_worked():
+    #        row: 0  1  2  3  4  5  6  7  8  9
+    mask = np.array([1, 0, 1, 1, 1, 1, 0, 1, 1, 1], dtype=np.uint8)
+    ids = np.array([4, 9, 7, -1, 0, 2, 2, 8, 3, 1])          # V = 8: rows 3 (id -1) and 7 (id 8) are out of range
+    cu = np.array([0, 3, 3, 8, 10])
+    out = orc.compact_rows(mask, ids, cu, V=8)
+    assert out["row_map"].tolist() == [0, 2, 4, 5, 8, 9]
+    assert out["seq_len"].tolist() == [2, 0, 2, 2]
+    assert (out["n_bad_token"], out["n_bad_seq"], out["n_bad_group"]) == (2, 0, 0)
+    # a prompt index out of range empties its sequence (and its out-of-range ids are no longer looked at)
+    out = orc.compact_rows(mask, ids, cu, V=8, group_idx=[0, 1, 2, 1], P=2)
+    assert out["row_map"].tolist() == [0, 2, 8, 9]
+    assert out["seq_len"].tolist() == [2, 0, 0, 2]
+    assert (out["n_bad_token"], out["n_bad_seq"], out["n_bad_group"]) == (0, 0, 1)
+    # broken offsets: [0,3) kept, [3,2) decreasing, [2,8) starts below the earlier offset 3, [8,10) kept
+    out = orc.compact_rows(mask, ids, np.array([0, 3, 2, 8, 10]), V=8)
+    assert out["row_map"].tolist() == [0, 2, 8, 9]
+    assert out["seq_len"].tolist() == [2, 0, 0, 2] and out["n_bad_seq"] == 2 and out["n_bad_token"] == 0
+
+
+def test_compact_rows_against_library_routines():
+    rng = np.random.default_rng(51)
+    R, V = 200, 50
+    mask = (rng.random(R) < 0.6).astype(np.uint8)
+    ids = rng.integers(-3, V + 3, size=R)
+    cuts = np.sort(rng.integers(0, R + 1, size=7))
+    cu = np.concatenate([[0], cuts, [R]])
+    out = orc.compact_rows(mask, ids, cu, V)
+    keep = (mask != 0) & (ids >= 0) & (ids < V)
+    np.testing.assert_array_equal(out["row_map"], np.flatnonzero(keep))     # clean offsets: plain stream compaction
+    np.testing.assert_array_equal(out["seq_len"], np.add.reduceat(np.append(keep, 0).astype(np.int64), cu[:-1]) * (np.diff(cu) > 0))
+    assert out["n_bad_token"] == int(((mask != 0) & ~keep).sum())
+    np.testing.assert_array_equal(orc.compact_rows(mask, np.clip(ids, 0, V - 1), cu, V)["seq_len"], orc.segment_lengths(mask, cu))
+    g = rng.integers(-1, 6, size=40)
+    np.testing.assert_array_equal(orc.group_count(g, 5), np.bincount(g[(g >= 0) & (g < 5)], minlength=5))
+
+
+def test_target_logit_is_the_gathered_entry_of_the_logits():
+    rng = np.random.default_rng(52)
+    X, W, ids = _rand_problem(rng, R=13, H=6, V=10)
+    mask = (rng.random(13) < 0.8).astype(np.uint8); mask[0] = 1
+    for tau in (1.0, 0.6):
+        zy = orc.target_logit(X, W, ids, mask, temperature=tau)
+        Z = np.einsum("th,vh->tv", X, W) / tau
+        np.testing.assert_allclose(zy, np.take_along_axis(Z, ids[:, None], 1)[:, 0] * (mask != 0), atol=1e-14)
+        lp, lse = orc.token_logprob(X, W, ids, mask, temperature=tau)
+        np.testing.assert_allclose(zy, lp + lse, atol=1e-13)
+    # hand value: row 0 of the worked example reads logit ln 2 for target 0
+    Ww, Xw, idw, mw, _, _ = _worked()
+    np.testing.assert_allclose(orc.target_logit(Xw, Ww, idw, mw), [LN2, LN4, 0.0], atol=1e-15)
+
+
+def test_weight_grad_rows_are_rows_of_the_autograd_gradient():
+    rng = np.random.default_rng(53)
+    R, H, V = 14, 5, 9
+    X, W, ids = _rand_problem(rng, R=R, H=H, V=V)
+    mask = (rng.random(R) < 0.8).astype(np.uint8)
+    c = rng.normal(size=R)
+    for tau in (1.0, 0.7):
+        _, lse = orc.token_logprob(X, W, ids, np.ones(R, np.uint8), temperature=tau)
+        Xt = torch.tensor(X); Wt = torch.tensor(W, requires_grad=True)
+        lsm = torch.log_softmax(Xt @ Wt.T / tau, dim=1)
+        (torch.tensor(c * (mask != 0)) * lsm[torch.arange(R), torch.from_numpy(ids)]).sum().backward()
+        vs = np.array([0, V - 1, 4, int(ids[np.flatnonzero(mask)[0]])])
+        got = orc.weight_grad_rows(X, W[vs], vs, ids, mask, lse, c, temperature=tau)
+        np.testing.assert_allclose(got, Wt.grad.numpy()[vs], atol=1e-13)
+        # a plain sum over rows: two row blocks add up to the whole
+        a = orc.weight_grad_rows(X[:6], W[vs], vs, ids[:6], mask[:6], lse[:6], c[:6], temperature=tau)
+        b = orc.weight_grad_rows(X[6:], W[vs], vs, ids[6:], mask[6:], lse[6:], c[6:], temperature=tau)
+        np.testing.assert_allclose(a + b, got, atol=1e-13)
+    # worked example (the GRPO coefficients [0, -0.375, 0.125], lse = ln 6): same rows as the full backward
+    Ww, Xw, idw, mw, _, _ = _worked()
+    cw = np.array([0.0, -0.375, 0.125])
+    x1, x2 = np.array([0.0, LN4]), np.array([LN2, LN3])
+    exp_dW = np.stack([0.0625 * x1 - x2 / 24, -0.125 * x1 - x2 / 16, 0.0625 * x1 + 5 * x2 / 48])
+    np.testing.assert_allclose(orc.weight_grad_rows(Xw, Ww[[2, 0]], [2, 0], idw, mw, np.full(3, math.log(6.0)), cw), exp_dW[[2, 0]], atol=1e-14)
