@@ -159,6 +159,9 @@ def main():
     ap.add_argument("--path", default="policy-loss", choices=["policy-loss", "logz-head", "rvq-encode"],
                     help="logz-head: time the small upstream head (forward + backward) instead of the hot path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="time only the headline (objective, backward) pair, not the other objective and the recompute backward")
+    ap.add_argument("--secondary-steps", type=int, default=5, help="timed steps of each secondary measurement (3 warm-ups each)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region, run one plain 1 GiB device copy (reference dispatch for FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
@@ -179,34 +182,32 @@ def main():
         return bench_rvq_encode(a, dev)
     b = synth.make_rollouts(a.config, dev, a.layout, len_div=a.len_div)
     cfg = b.cfg
-    obj = binding.OBJECTIVES[a.objective]
     batch = binding.make_batch(b.hidden, b.weight, b.token_ids, b.mask, b.cu_seqlens, b.group_idx, b.rewards,
                                b.old_logprob, b.ref_logprob, b.log_z, cfg.P)
-    prm = binding.make_params(cfg.clip_eps, cfg.kl_coef, cfg.beta, cfg.adv_eps, cfg.adv_std_ddof, a.chunk_rows,
-                              backward_mode=a.backward, max_seq_len=int(b.lengths.max()))
-    plan = binding.PolicyLossPlan(batch, prm, dev, b.hidden.dtype, backward=True)
 
-    for _ in range(a.warmup):
-        plan.run(obj)
-    torch.cuda.synchronize()
-    binding.rl_profile_enable(True)
-    binding.rl_profile_read()
-    torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(a.steps + 1)]   # on the stream the library launches on
-    t0 = time.perf_counter()
-    marks[0].record()
-    for i in range(a.steps):
-        res = plan.run(obj)
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(a.steps))
-    prof = binding.rl_profile_read()
-    binding.rl_profile_enable(False)
+    # headline: the objective and backward mode asked for (default: GRPO, auto = single pass)
+    head = time_mode(a, b, batch, a.objective, a.backward, a.steps, a.warmup)
 
     # what a pure MFMA loop with toggling random operands reaches on this part right now (no memory traffic)
     peak_burst = binding.rl_measure_mfma_peak(200, dev)
     peak_sustained = binding.rl_measure_mfma_peak(1000, dev)
+
+    # the other half of the target, timed the same way in the same run: the other objective in the same mode, and the
+    # backward that recomputes the logits tile by tile (the problem statement's wording; four contractions instead of three)
+    secondary = {}
+    if not a.no_secondary:
+        other = "flow" if a.objective == "grpo" else "grpo"
+        for key, objective, backward in ((f"{other}_{a.backward}", other, a.backward),
+                                         (f"{a.objective}_recompute", a.objective, "recompute"),
+                                         (f"{other}_recompute", other, "recompute")):
+            if (backward == a.backward and objective == a.objective) or key in secondary:
+                continue
+            r = time_mode(a, b, batch, objective, backward, a.secondary_steps, 3)
+            secondary[key] = {k: r[k] for k in ("objective", "backward", "backward_resolved", "steps", "warmup", "value", "unit",
+                                                 "ms_per_step", "ms_per_step_median", "ms_per_step_min", "mfma_frac_6THV",
+                                                 "tflops_6THV", "roofline", "loss")}
+            secondary[key]["class_ms_per_step"] = {k: round(v["ms_per_step"], 3) for k, v in r["kernels"].items() if v["ms_per_step"] > 0}
+            secondary[key]["class_tflops"] = {k: round(v["tflops"], 1) for k, v in r["kernels"].items() if v["tflops"]}
 
     if a.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -215,6 +216,65 @@ def main():
         dst.copy_(src)                      # 1 GiB read + 1 GiB written
         torch.cuda.synchronize()
         del src, dst
+
+    T = head["T"]
+    achieved = head["roofline"]["achieved"]
+    out = {
+        "metric": "rollout tokens/sec, fused logprob+policy-loss fwd+bwd; % bf16 MFMA peak",
+        "value": head["value"], "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": head["ms_per_step"], "ms_per_step_median": head["ms_per_step_median"], "ms_per_step_min": head["ms_per_step_min"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{a.config}: P={cfg.P} G={cfg.G} len U[{cfg.len_lo},{cfg.len_hi}] H={cfg.H} V={cfg.V} "
+                               f"{cfg.dtype}, {a.layout} rows R={b.R}, real tokens T={T}, objective={a.objective}, "
+                               f"backward={head['backward_resolved']}"
+                               + (f", len_div={a.len_div}" if a.len_div != 1 else ""),
+                   "objective": a.objective, "layout": a.layout, "T": T, "R": b.R, "H": cfg.H, "V": cfg.V,
+                   "chunk_rows": head["chunk_rows"], "backward": a.backward, "backward_resolved": head["backward_resolved"]},
+        "mfma_frac_6THV": head["mfma_frac_6THV"],
+        "tflops_6THV": head["tflops_6THV"],
+        "roofline": head["roofline"],
+        "mfma_only_measured": {"burst_200ms": {"tflops": peak_burst[0], "shader_mhz": peak_burst[1]},
+                               "sustained_1s": {"tflops": peak_sustained[0], "shader_mhz": peak_sustained[1]},
+                               "roofline_frac_of_sustained": achieved / peak_sustained[0] if peak_sustained[0] > 0 else None},
+        "kernels": head["kernels"],
+        "hbm_bound_classes": head["hbm_bound_classes"],
+        "loss": head["loss"],
+        "secondary": secondary,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(a.config, a.objective)
+    print(json.dumps(out), flush=True)
+
+
+def time_mode(a, b, batch, objective: str, backward: str, steps: int, warmup: int) -> dict:
+    """`warmup` untimed and `steps` timed calls of rl_policy_loss_fwd_bwd for one objective and backward mode, between
+    synchronisations; per-class launch times from HIP events the library records on its own stream."""
+    import torch
+    from paper_2603_16435_amd import binding
+    cfg = b.cfg
+    dev = b.hidden.device
+    obj = binding.OBJECTIVES[objective]
+    prm = binding.make_params(cfg.clip_eps, cfg.kl_coef, cfg.beta, cfg.adv_eps, cfg.adv_std_ddof, a.chunk_rows,
+                              backward_mode=backward, max_seq_len=int(b.lengths.max()))
+    plan = binding.PolicyLossPlan(batch, prm, dev, b.hidden.dtype, backward=True)
+    for _ in range(warmup):
+        plan.run(obj)
+    torch.cuda.synchronize()
+    binding.rl_profile_enable(True)
+    binding.rl_profile_read()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]   # on the stream the library launches on
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        res = plan.run(obj)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    prof = binding.rl_profile_read()
+    binding.rl_profile_enable(False)
 
     # launches per step that have rows to work on (the library launches a fixed upper bound of chunks; the rest return at once)
     stash = prof["gemm_bwd"][1] > 0
@@ -228,11 +288,10 @@ def main():
             rows += n
     else:
         real_chunks = -(-b.T // tc)
-    T = int(res.stats_dict()["n_tokens"])
+    st = res.stats_dict()
+    T = int(st["n_tokens"])
     loss = float(res.loss.item())
-    assert T == b.T and loss == loss, (T, b.T, loss)
-    ms_step = dt / a.steps * 1e3
-    tok_s = T * a.steps / dt
+    assert T == b.T and loss == loss and st["n_overflow_rows"] == 0, (T, b.T, loss, st)
     thv = float(T) * cfg.H * cfg.V
     peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_F32_TFLOPS
     # dominant kernel: the contraction class with the largest share of the step
@@ -241,9 +300,9 @@ def main():
     gemms = {k: prof[k] for k in class_flops}
     dom = max(gemms, key=lambda k: gemms[k][0])
     dom_ms, dom_n = gemms[dom]
-    achieved = class_flops[dom] * a.steps / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
-    kernels = {k: {"ms_per_step": v[0] / a.steps, "launches_per_step": v[1] / a.steps,
-                   "tflops": (class_flops[k] * a.steps / (v[0] * 1e-3) / 1e12) if (k in gemms and v[0] > 0) else None}
+    achieved = class_flops[dom] * steps / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    kernels = {k: {"ms_per_step": v[0] / steps, "launches_per_step": v[1] / steps,
+                   "tflops": (class_flops[k] * steps / (v[0] * 1e-3) / 1e12) if (k in gemms and v[0] > 0) else None}
                for k, v in prof.items()}
     # The O(T) launch classes against the HBM roofline: algorithmic bytes per step (what the stage must read and
     # write once, from the shapes) / event-timed duration.  They are launch-latency-bound at these sizes.
@@ -263,42 +322,37 @@ def main():
     }
     hbm = {}
     for k, nbytes in class_bytes.items():
-        ms = prof[k][0] / a.steps
+        ms = prof[k][0] / steps
         if ms > 0:
             gbps = nbytes / (ms * 1e-3) / 1e9
             hbm[k] = {"ms_per_step": ms, "algorithmic_bytes_per_step": nbytes, "gbps": gbps, "frac_of_8TBps": gbps / 8000.0}
+    mode_key = "stash" if stash else "recompute"
+    kernel_name = {"gemm_fwd": "gemm_nt_bf16_kernel<EpiFwdStash>" if stash else "gemm_nt_bf16_kernel<EpiFwd>",
+                   "gemm_ds": "gemm_nt_bf16_kernel<EpiDS>", "gemm_dx": "gemm_nt_bf16_kernel<EpiDX>",
+                   "gemm_dw": "gemm_nt_bf16_kernel<EpiDW>", "gemm_bwd": "gemm_nt_bf16_pair_kernel<EpiDX, EpiDW>"}[dom]
     out = {
-        "metric": "rollout tokens/sec, fused logprob+policy-loss fwd+bwd; % bf16 MFMA peak",
-        "value": tok_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms_step, "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{a.config}: P={cfg.P} G={cfg.G} len U[{cfg.len_lo},{cfg.len_hi}] H={cfg.H} V={cfg.V} "
-                               f"{cfg.dtype}, {a.layout} rows R={b.R}, real tokens T={T}, objective={a.objective}"
-                               + (f", len_div={a.len_div}" if a.len_div != 1 else ""),
-                   "objective": a.objective, "layout": a.layout, "T": T, "R": b.R, "H": cfg.H, "V": cfg.V,
-                   "chunk_rows": tc, "backward": a.backward},
-        "mfma_frac_6THV": 6.0 * thv / (dt / a.steps) / 1e12 / peak,
-        "tflops_6THV": 6.0 * thv / (dt / a.steps) / 1e12,
-        "roofline": {"bound": "mfma", "kernel": f"gemm_nt_bf16_kernel ({dom})", "achieved": achieved, "peak": peak,
+        "objective": objective, "backward": backward, "backward_resolved": "single-pass" if stash else "recompute",
+        "steps": steps, "warmup": warmup, "T": T, "chunk_rows": tc,
+        "value": T * steps / dt, "unit": "tokens/s",
+        "ms_per_step": dt / steps * 1e3, "ms_per_step_median": step_ms[len(step_ms) // 2], "ms_per_step_min": step_ms[0],
+        "mfma_frac_6THV": 6.0 * thv / (dt / steps) / 1e12 / peak,
+        "tflops_6THV": 6.0 * thv / (dt / steps) / 1e12,
+        "roofline": {"bound": "mfma", "kernel": f"{kernel_name} ({dom})", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": (MEASURED_TRAFFIC_7B["stash" if stash else "recompute"].get(dom)
+                     "traffic": (MEASURED_TRAFFIC_7B[mode_key].get(dom)
                                  if (a.config == "7b" and a.len_div == 1 and a.layout == "padded"
                                      and tc == default_tc) else None),
                      "traffic_note": "HBM-side bytes of the largest launch of this class (rocprofv3 FETCH_SIZE/WRITE_SIZE, profiles/gemm_nt_bf16_7b.md)",
-                     "launches_with_work": real_chunks * a.steps, "launches": int(dom_n),
-                     "avg_launch_ms": dom_ms / max(real_chunks * a.steps, 1),
+                     "launches_with_work": real_chunks * steps, "launches": int(dom_n),
+                     "avg_launch_ms": dom_ms / max(real_chunks * steps, 1),
                      "flops_per_avg_launch": class_flops[dom] / real_chunks},
-        "mfma_only_measured": {"burst_200ms": {"tflops": peak_burst[0], "shader_mhz": peak_burst[1]},
-                               "sustained_1s": {"tflops": peak_sustained[0], "shader_mhz": peak_sustained[1]},
-                               "roofline_frac_of_sustained": achieved / peak_sustained[0] if peak_sustained[0] > 0 else None},
         "kernels": kernels,
         "hbm_bound_classes": hbm,
         "loss": loss,
     }
-    if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(a.config, a.objective)
-    print(json.dumps(out), flush=True)
+    del plan, res
+    torch.cuda.empty_cache()
+    return out
 
 
 if __name__ == "__main__":

@@ -32,9 +32,10 @@
  *  - Masked rows: logprob = lse = 0, d_hidden row = 0, no contribution anywhere.
  *  - Host-checkable errors (null pointers, sizes, dtype, objective, clip range, workspace
  *    size) are returned before anything is launched.  Data errors found on the device
- *    (token id outside [0,V), group index outside [0,P), decreasing cu_seqlens) never
+ *    (token id outside [0,V), group index outside [0,P), broken cu_seqlens) never
  *    cause an out-of-bounds access: the offending row / sequence is treated as masked /
- *    empty and counted in rl_stats.
+ *    empty and counted in rl_stats.  A sequence keeps its rows iff 0 <= cu[i] <= cu[i+1] <= R
+ *    and cu[i] is not below any earlier offset, so kept ranges never overlap.
  *  - Results are bit-reproducible run to run: no floating-point atomics are used.
  *  - bf16 inputs need H % 8 == 0 (16-byte rows); f32 inputs need H % 4 == 0.
  */
@@ -55,7 +56,8 @@ typedef enum rl_status {
   RL_ERR_DTYPE = 3,       /* unknown rl_dtype                                   */
   RL_ERR_RANGE = 4,       /* objective / clip_eps / ddof / backward mode out of range */
   RL_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than needed  */
-  RL_ERR_HIP = 6          /* a HIP launch failed (see hipGetLastError)          */
+  RL_ERR_HIP = 6,         /* a HIP launch failed (see hipGetLastError)          */
+  RL_ERR_UNIMPLEMENTED = 7 /* a valid request this build has no kernel for (RL_BWD_STASH with f32 inputs or H % 128 != 0) */
 } rl_status;
 
 typedef enum rl_objective { RL_OBJ_GRPO = 0, RL_OBJ_FLOW = 1 } rl_objective;
@@ -69,11 +71,13 @@ typedef enum rl_dtype { RL_F32 = 0, RL_BF16 = 1 } rl_dtype;
  *                    precision (ref_t = target logit - old log-prob, i.e. the row's logsumexp up to
  *                    the drift between old and current policy), and dX / dW are contracted from
  *                    that store (three contractions per chunk, the 6 T H V flops the path needs).
- *                    Needs bf16 inputs, H a multiple of 128, 16-byte aligned hidden / weight and
- *                    0 < params->max_seq_len <= chunk rows; otherwise RL_ERR_RANGE.  old_logprob only
- *                    steers the reference (clamped to [-40, 0]): the stored probabilities stay
+ *                    Needs bf16 inputs, H a multiple of 128 and 16-byte aligned hidden / weight (otherwise
+ *                    RL_ERR_UNIMPLEMENTED) and 0 < params->max_seq_len <= chunk rows (otherwise RL_ERR_RANGE).
+ *                    old_logprob only steers the reference (clamped to [-40, 0]): the stored probabilities stay
  *                    representable while the current log-prob of the sampled token is above about
- *                    -120 nats; beyond that the loss comes back non-finite rather than wrong.
+ *                    -100 nats.  A row beyond that is counted in rl_stats.n_overflow_rows and the loss of the
+ *                    call comes back NaN (its gradient rows are not numbers): the caller re-runs the batch with
+ *                    RL_BWD_RECOMPUTE, which has no such limit.
  *  RL_BWD_AUTO       RL_BWD_STASH when its conditions hold, else RL_BWD_RECOMPUTE.
  * Either way at most chunk_rows x V values are held at a time, never T x V. */
 typedef enum rl_aggregation { RL_AGG_SEQUENCE = 0, RL_AGG_TOKEN = 1 } rl_aggregation;
@@ -104,7 +108,7 @@ typedef struct rl_params {
   float   beta;                 /* FLOW only: reward scale                               */
   float   adv_eps;              /* added to the group std                                */
   int32_t adv_std_ddof;         /* 0 (population std) or 1                               */
-  int32_t chunk_rows;           /* rows staged at once; 0 = library default (32768; 40960 in single-pass mode) */
+  int32_t chunk_rows;           /* rows staged at once; 0 = library default (rl_default_chunk_rows / _single_pass) */
                                 /* rounded up to a multiple of 256; sizes the workspace  */
   float   clip_eps_high;        /* upper bound of the ratio / weight is 1 + clip_eps_high; 0 = clip_eps (symmetric) */
   int32_t aggregation;          /* GRPO: RL_AGG_SEQUENCE (mean over sequences of the token mean) or         */
@@ -129,7 +133,8 @@ typedef struct rl_stats {       /* device struct written by the loss call       
   int32_t n_bad_group;          /* sequences dropped because group_idx was out of range  */
   int32_t n_bad_seq;            /* sequences treated as empty (cu_seqlens decreasing / out of [0,R]) */
   int32_t n_seq_too_long;       /* sequences longer than params->max_seq_len (single-pass backward): loss is then NaN */
-  int32_t reserved[1];
+  int32_t n_overflow_rows;      /* single-pass backward: rows whose stored probabilities left the representable range  */
+                                /* (sum outside [1e-30, 1e30] or not a number): loss is then NaN                       */
 } rl_stats;
 
 typedef struct rl_outputs {     /* NULL = not wanted, except loss                        */
@@ -145,6 +150,14 @@ typedef struct rl_outputs {     /* NULL = not wanted, except loss               
   float*    d_log_z;            /* [P]   zero for GRPO                                   */
   rl_stats* stats;              /* [1]                                                   */
   float*    entropy;            /* [R]   entropy of softmax(W x_t), from the forward pass' online sums */
+  /* Index work of the path, for callers that want to check it bit for bit: */
+  int32_t*  row_map;            /* [R]   entry k < T: original row of the k-th counting row (sequence by sequence, rows  */
+                                /*       ascending); entries T..R-1 are -1                                               */
+  int32_t*  group_count;        /* [P]   sequences naming each prompt                                                    */
+  int32_t*  target_col;         /* [R]   vocabulary entry the target logit of the row was read from (the accumulator's   */
+                                /*       own position in the logits tile, or the row of W in single-pass mode): equals   */
+                                /*       token_ids on counting rows, -1 elsewhere                                        */
+  float*    target_logit;       /* [R]   z_t[y_t] (tempered), 0 on rows that do not count                                */
 } rl_outputs;
 
 /* Bytes of device workspace the two calls below need for this batch shape (host only; reads
@@ -173,28 +186,6 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* batch, const rl_params* params,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 const char* rl_status_string(int32_t status);
-
-/* Optional timing of the library's own launches, for benchmarks (not thread-safe; the only
- * place the library creates objects of its own: HIP events, kept for reuse).  While enabled,
- * every group of launches of the two calls above is bracketed by a pair of events recorded on
- * the caller's stream.  rl_profile_read waits for the recorded events, adds up elapsed
- * milliseconds and bracket counts per class since the previous read, and clears the list. */
-enum { RL_PROF_PREP = 0,       /* counts, scan, compaction, output zero-fill            */
-       RL_PROF_GEMM_FWD = 1,   /* forward logits contraction + online partial softmax   */
-       RL_PROF_COMBINE = 2,    /* partials -> lse, logp                                 */
-       RL_PROF_LOSS = 3,       /* advantage, per-sequence loss, final reduce            */
-       RL_PROF_TRANSPOSE = 4,  /* W^T, X^T chunks, zeroing masked dX rows               */
-       RL_PROF_GEMM_DS = 5,    /* recomputed logits -> dS                               */
-       RL_PROF_GEMM_DX = 6,    /* dX = dS W                                             */
-       RL_PROF_GEMM_DW = 7,    /* dW += dS^T X                                          */
-       RL_PROF_GEMM_BWD = 8,   /* single-pass backward: dX and dW of a chunk in one launch */
-       RL_PROF_CLASSES = 9 };
-typedef struct rl_profile {     /* host struct */
-  double  ms[RL_PROF_CLASSES];
-  int64_t launches[RL_PROF_CLASSES];
-} rl_profile;
-void rl_profile_enable(int32_t on);
-rl_status rl_profile_read(rl_profile* out);
 
 /* Library version (major*100 + minor) and the chunk sizes used when chunk_rows = 0 (recompute mode; single-pass mode). */
 int32_t rl_version(void);
@@ -238,22 +229,6 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
 rl_status rl_rvq_codebook_norms(const void* codebooks, int32_t G, int32_t N, int32_t S, int32_t D, float* norms, void* stream);
 rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,
                         int32_t N, int32_t S, int32_t* codes, void* residual, void* stream);
-
-/* Benchmark aid: runs a pure bf16 MFMA issue loop (v_mfma_f32_16x16x32_bf16 in the hot kernel's 8 x 8 register
- * blocking, pseudo-random operands, four wavefronts per CU, no memory traffic) for about `millis` ms on
- * `stream`, SYNCHRONISES on it, and returns the rate it reached and the shader clock it ran at.  This is
- * the ceiling any MFMA-bound kernel can approach on this part at this moment (clock throttling included).
- * scratch: device buffer of at least 1 MiB owned by the caller. */
-rl_status rl_measure_mfma_peak(int32_t millis, void* scratch, size_t scratch_bytes, void* stream,
-                               double* tflops, double* shader_mhz);
-
-/* Diagnostic (host only, nothing is launched): the workgroup -> tile map of the contraction kernels, for tests.
- * tiles_m x tiles_n tiles, bands of group_m M-tiles, by_share = 0 (eight equal runs of the band sequence) or 1
- * (each of the eight accelerator dies owns a share of the M-tiles).  *workgroups receives the launch size;
- * tile[2 w] / tile[2 w + 1] (caller's array of 2 * launch size ints, or NULL to query the size only) receive
- * the (m, n) tile of workgroup w, or (-1, -1) if it has none. */
-rl_status rl_debug_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t group_m, int32_t by_share,
-                              int32_t* workgroups, int32_t* tile);
 
 #ifdef __cplusplus
 }

@@ -191,11 +191,12 @@ def weight_grad_rows(hidden, weight_rows, vocab_rows, token_ids, mask, lse, c, t
     m = np.asarray(mask).astype(bool)
     lse = np.asarray(lse, dtype=np.float64); c = np.asarray(c, dtype=np.float64)
     rows = np.nonzero(m)[0]
-    Z = X[rows] @ Wr.T / temperature                       # [n_rows, n] logits of the sampled vocabulary entries
+    Xr = X if rows.size == m.size else X[rows]             # (no copy of a block in which every row counts)
+    Z = Xr @ Wr.T / temperature                            # [n_rows, n] logits of the sampled vocabulary entries
     dS = -np.exp(Z - lse[rows][:, None])
     dS += (ids[rows][:, None] == vs[None, :])
     dS *= (c[rows] / temperature)[:, None]
-    return dS.T @ X[rows]
+    return dS.T @ Xr
 
 
 # --------------------------------------------------------------------------

@@ -39,14 +39,15 @@ class rl_params(C.Structure):
 class rl_stats(C.Structure):
     _fields_ = [("n_tokens", C.c_int32), ("n_clip_hi", C.c_int32), ("n_clip_lo", C.c_int32),
                 ("n_bad_token", C.c_int32), ("n_bad_group", C.c_int32), ("n_bad_seq", C.c_int32),
-                ("n_seq_too_long", C.c_int32), ("reserved", C.c_int32 * 1)]
+                ("n_seq_too_long", C.c_int32), ("n_overflow_rows", C.c_int32)]
 
 
 class rl_outputs(C.Structure):
     _fields_ = [("loss", C.c_void_p), ("seq_loss", C.c_void_p), ("logprob", C.c_void_p), ("lse", C.c_void_p),
                 ("advantages", C.c_void_p), ("seq_len", C.c_void_p), ("coeff", C.c_void_p),
                 ("d_hidden", C.c_void_p), ("d_weight", C.c_void_p), ("d_log_z", C.c_void_p), ("stats", C.c_void_p),
-                ("entropy", C.c_void_p)]
+                ("entropy", C.c_void_p), ("row_map", C.c_void_p), ("group_count", C.c_void_p), ("target_col", C.c_void_p),
+                ("target_logit", C.c_void_p)]
 
 
 PROF_CLASSES = ("prep", "gemm_fwd", "combine", "loss", "transpose", "gemm_ds", "gemm_dx", "gemm_dw", "gemm_bwd")
@@ -56,7 +57,7 @@ class rl_profile(C.Structure):
     _fields_ = [("ms", C.c_double * 9), ("launches", C.c_int64 * 9)]
 
 
-STATS_FIELDS = ("n_tokens", "n_clip_hi", "n_clip_lo", "n_bad_token", "n_bad_group", "n_bad_seq", "n_seq_too_long")
+STATS_FIELDS = ("n_tokens", "n_clip_hi", "n_clip_lo", "n_bad_token", "n_bad_group", "n_bad_seq", "n_seq_too_long", "n_overflow_rows")
 BACKWARD_MODES = {"auto": 0, "recompute": 1, "stash": 2}
 
 _lib = None
@@ -227,6 +228,10 @@ class LossResult:
     d_log_z: torch.Tensor
     stats: torch.Tensor          # int32[8]: see STATS_FIELDS
     entropy: Optional[torch.Tensor] = None
+    row_map: Optional[torch.Tensor] = None       # int32[R]: first T entries = original rows of the counting rows, rest -1
+    group_count: Optional[torch.Tensor] = None   # int32[P]
+    target_col: Optional[torch.Tensor] = None    # int32[R]: vocabulary entry the target logit was read from, -1 on other rows
+    target_logit: Optional[torch.Tensor] = None  # float32[R]
 
     def stats_dict(self):
         v = self.stats.cpu().tolist()
@@ -236,7 +241,7 @@ class LossResult:
 class PolicyLossPlan:
     """Pre-allocated outputs + workspace for repeated calls on one batch shape (timing loops)."""
 
-    def __init__(self, batch: rl_batch, params: rl_params, device, hidden_dtype, backward=True):
+    def __init__(self, batch: rl_batch, params: rl_params, device, hidden_dtype, backward=True, index_outputs=False):
         R, H, V, B, P = batch.R, batch.H, batch.V, batch.B, batch.P
         f32 = dict(dtype=torch.float32, device=device)
         self.res = LossResult(
@@ -247,6 +252,10 @@ class PolicyLossPlan:
             d_weight=torch.empty((V, H), **f32) if backward else None,
             d_log_z=torch.empty(P, **f32), stats=torch.zeros(8, dtype=torch.int32, device=device),
             entropy=torch.empty(R, **f32))
+        if index_outputs:
+            i32 = dict(dtype=torch.int32, device=device)
+            self.res.row_map, self.res.group_count = torch.empty(R, **i32), torch.empty(P, **i32)
+            self.res.target_col, self.res.target_logit = torch.empty(R, **i32), torch.empty(R, **f32)
         self.ws = _workspace(rl_workspace_bytes(batch, params, backward), device)
         o = rl_outputs()
         r = self.res
@@ -256,6 +265,9 @@ class PolicyLossPlan:
         o.d_weight = r.d_weight.data_ptr() if backward else None
         o.d_log_z, o.stats = r.d_log_z.data_ptr(), r.stats.data_ptr()
         o.entropy = r.entropy.data_ptr()
+        if index_outputs:
+            o.row_map, o.group_count = r.row_map.data_ptr(), r.group_count.data_ptr()
+            o.target_col, o.target_logit = r.target_col.data_ptr(), r.target_logit.data_ptr()
         self.out = o
         self.batch, self.params = batch, params
 
@@ -289,13 +301,13 @@ def rl_policy_loss_fwd_bwd(objective, hidden, weight, token_ids, mask, cu_seqlen
                            clip_eps=0.2, kl_coef=1e-3, beta=15.0, adv_eps=1e-6, adv_std_ddof=0,
                            chunk_rows=0, backward=True, backward_mode="auto", max_seq_len=0, clip_eps_high=0.0,
                            aggregation="sequence", ratio_level="token", flow_weight_norm="sum",
-                           temperature=0.0) -> LossResult:
+                           temperature=0.0, index_outputs=False) -> LossResult:
     """One pass of the whole path.  `objective` is "grpo" | "flow" (or the enum value)."""
     obj = OBJECTIVES[objective] if isinstance(objective, str) else int(objective)
     b = make_batch(hidden, weight, token_ids, mask, cu_seqlens, group_idx, rewards, old_logprob, ref_logprob, log_z, P)
     prm = make_params(clip_eps, kl_coef, beta, adv_eps, adv_std_ddof, chunk_rows, backward_mode, max_seq_len,
                       clip_eps_high, aggregation, ratio_level, flow_weight_norm, temperature)
-    plan = PolicyLossPlan(b, prm, hidden.device, hidden.dtype, backward)
+    plan = PolicyLossPlan(b, prm, hidden.device, hidden.dtype, backward, index_outputs)
     return plan.run(obj)
 
 

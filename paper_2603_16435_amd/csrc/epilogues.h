@@ -46,6 +46,7 @@ struct EpiFwd {
   int ldp;              // = chunk rows
   int V;
   float zs;             // inverse temperature
+  int* ycol_c;          // [compact row] vocabulary row the target logit was taken from (the position of the accumulator read)
 
   // one token column of one lane: the MB * kRegs logits it holds.  PAD: some of the sub-tile's rows are
   // vocabulary padding (only in the last tile row) and must not enter the sums.
@@ -93,14 +94,16 @@ struct EpiFwd {
       const int yrel = valid ? ids_c[d.chunk_start + n] - c.m0 : -1;
       if (yrel >= 0 && yrel < MB * L::kBlk && L::owns(yrel, c.lane)) {
         float zy = 0.f;
+        int got = -1;
 #pragma unroll
         for (int bi = 0; bi < MB; ++bi)
 #pragma unroll
           for (int i = 0; i < L::kRegs; ++i) {
             const float v = acc_read<AGPR>(acc[bi][bj], i);
-            if (L::row(bi, i, c.lane) == yrel) zy = v;
+            if (L::row(bi, i, c.lane) == yrel) { zy = v; got = c.m0 + L::row(bi, i, c.lane); }
           }
         zy_c[d.chunk_start + n] = zy * zs;
+        ycol_c[d.chunk_start + n] = got;
       }
       float mx, sm, su;
       if (pad) column<L, MB, NB, AGPR, true>(acc, bj, c.lane, vleft, mx, sm, su);

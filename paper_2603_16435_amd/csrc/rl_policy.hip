@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "../../include/rl_policy.h"
+#include "../../include/rl_policy_diag.h"
 #include "epilogues.h"
 #include "logz_head.h"
 #include "rvq_encode.h"
@@ -49,7 +50,8 @@ struct TuneDW     { static constexpr int kBand = 1, kPfd = 2, kVmg = 4, kVmo = 1
 struct Ctrl {            // device control block at the head of the workspace
   int n_real;
   int too_long;          // single-pass backward: some sequence has more rows than the caller promised / a chunk holds
-  int pad[14];
+  int overflow;          // single-pass backward: rows whose stored probabilities left the range of the staging precision
+  int pad[13];
 };
 
 struct ChunkDesc {       // device record of one sequence-aligned chunk (single-pass backward)
@@ -118,8 +120,33 @@ __device__ inline double block_sum(double v, double* sh) {   // blockDim.x multi
 }
 
 // ------------------------------------------------------------------ prep
+// Inclusive running maximum of the sequence offsets, hi[i] = max(cu[0..i]) for i < B (single workgroup of 1024).
+// A sequence keeps its rows only if its first offset is not below any earlier offset: the kept row ranges are then
+// pairwise disjoint whatever the offsets are, so no row can count twice and the compacted rows never exceed R.
+__global__ void cu_running_max_kernel(const int32_t* cu, int B, int32_t* hi) {
+  __shared__ int wmax[16];
+  __shared__ int carry;
+  if (threadIdx.x == 0) carry = INT32_MIN;
+  __syncthreads();
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int base = 0; base < B; base += 1024) {
+    const int i = base + threadIdx.x;
+    int x = i < B ? cu[i] : INT32_MIN;
+    for (int o = 1; o < 64; o <<= 1) { const int y = __shfl_up(x, o); if (lane >= o) x = max(x, y); }
+    if (lane == 63) wmax[w] = x;
+    __syncthreads();
+    int m = carry;
+    for (int k = 0; k < w; ++k) m = max(m, wmax[k]);
+    x = max(x, m);
+    if (i < B) hi[i] = x;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = x;
+    __syncthreads();
+  }
+}
+
 // One workgroup per sequence: validate its row range and group index, count rows that count.
-__global__ void seq_count_kernel(const uint8_t* mask, const int32_t* ids, const int32_t* cu,
+__global__ void seq_count_kernel(const uint8_t* mask, const int32_t* ids, const int32_t* cu, const int32_t* cu_hi,
                                  const int32_t* group_idx, int64_t R, int V, int P,
                                  int32_t* seq_len, rl_stats* stats) {
   const int i = blockIdx.x;
@@ -127,7 +154,7 @@ __global__ void seq_count_kernel(const uint8_t* mask, const int32_t* ids, const 
   if (threadIdx.x == 0) { sh_cnt = 0; sh_bad = 0; }
   __syncthreads();
   const int64_t a = cu[i], b = cu[i + 1];
-  const bool seq_ok = (a >= 0 && a <= b && b <= R);
+  const bool seq_ok = (a >= 0 && a <= b && b <= R && a >= cu_hi[i]);
   const bool grp_ok = (group_idx == nullptr) || (group_idx[i] >= 0 && group_idx[i] < P);
   int cnt = 0, bad = 0;
   if (seq_ok && grp_ok) {
@@ -176,6 +203,7 @@ __global__ void seq_scan_kernel(const int32_t* seq_len, int B, int32_t* cstart, 
     cstart[B] = carry;
     ctrl->n_real = carry;
     ctrl->too_long = 0;
+    ctrl->overflow = 0;
     if (stats) stats->n_tokens = carry;
   }
 }
@@ -184,7 +212,7 @@ __global__ void seq_scan_kernel(const int32_t* seq_len, int B, int32_t* cstart, 
 // compact row cstart[i]+k.  cpos[r] = compact position of original row r (left at -1 otherwise).
 __global__ void compact_kernel(const uint8_t* mask, const int32_t* ids, const int32_t* cu,
                                const int32_t* seq_len, const int32_t* cstart, int V,
-                               int32_t* row_map, int32_t* ids_c, int32_t* cpos) {
+                               int32_t* row_map, int32_t* ids_c, int32_t* cpos, int32_t* row_map_out) {
   const int i = blockIdx.x;
   if (seq_len[i] == 0) return;
   __shared__ int wsum[16];
@@ -207,6 +235,7 @@ __global__ void compact_kernel(const uint8_t* mask, const int32_t* ids, const in
     if (f) {
       const int c = carry + woff + pre;
       row_map[c] = (int)r; ids_c[c] = y; cpos[r] = c;
+      if (row_map_out) row_map_out[c] = (int)r;
     }
     __syncthreads();
     if (threadIdx.x == 0) carry += all;
@@ -228,11 +257,12 @@ __global__ void zero_masked_rows_kernel(const int32_t* cpos, T* dX, int64_t R, i
 // ------------------------------------------------------------------ advantage
 // Thread per prompt p: mean and std of the rewards of its members, then A_i for each member.
 __global__ void advantage_kernel(const float* rewards, const int32_t* group_idx, int B, int P,
-                                 float adv_eps, int ddof, float* adv) {
+                                 float adv_eps, int ddof, float* adv, int32_t* group_count) {
   const int p = blockIdx.x * blockDim.x + threadIdx.x;
   if (p >= P) return;
   int n = 0; double s = 0.0;
   for (int i = 0; i < B; ++i) if (group_idx[i] == p) { ++n; s += (double)rewards[i]; }
+  if (group_count) group_count[p] = n;
   if (n == 0) return;
   const double mu = s / n;
   double inv = 0.0;
@@ -270,13 +300,14 @@ __global__ void chunk_build_kernel(const int32_t* seq_len, const int32_t* cstart
 // (times the inverse temperature) and the reference of the stored probabilities, ref_t = zy_t - old_t, which is
 // the logsumexp of the row up to the (small) drift between the old and the current policy (NaN-free for any finite old_t).
 __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, const int32_t* row_map, const int32_t* ids_c,
-                                    const float* old_lp, const Ctrl* ctrl, float inv_tau, float* zy, float* ref_l2e) {
+                                    const float* old_lp, const Ctrl* ctrl, float inv_tau, float* zy, float* ref_l2e, int32_t* ycol) {
   const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (t >= ctrl->n_real) return;
   const int lane = threadIdx.x & 63;
   const int r = row_map[t];
   const uint4* x = reinterpret_cast<const uint4*>(X + (int64_t)r * H);
-  const uint4* w = reinterpret_cast<const uint4*>(W + (int64_t)ids_c[t] * H);
+  const int y = ids_c[t];
+  const uint4* w = reinterpret_cast<const uint4*>(W + (int64_t)y * H);
   float acc = 0.f;
   for (int k = lane; k < H / 8; k += 64) {
     const uint4 a = x[k], b = w[k];
@@ -294,6 +325,7 @@ __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, con
     const float o = fminf(fmaxf(old_lp[r], -40.f), 0.f);
     acc *= inv_tau;
     zy[t] = acc; ref_l2e[t] = (acc - o) * 1.4426950408889634f;
+    ycol[t] = y;                                   // the row of W the target logit was read from
   }
 }
 
@@ -302,8 +334,9 @@ __global__ void target_logit_kernel(const bf16_t* X, const bf16_t* W, int H, con
 // so it takes many short chains to keep the memory system busy), merged through LDS in a fixed order.
 constexpr int kSumSlices = 16;
 __global__ __launch_bounds__(64 * kSumSlices) void lse_sum_kernel(const float2* part, int ldp, int tiles_v, const float* zy_c, const float* ref_l2e,
-                               const int32_t* row_map, const ChunkDesc* desc,
-                               float* lse_c, float* logp_c, float* zsum_c, float* lse_out, float* logp_out, float* ent_out) {
+                               const int32_t* row_map, const ChunkDesc* desc, const int32_t* ycol_c, Ctrl* ctrl, rl_stats* stats,
+                               float* lse_c, float* logp_c, float* zsum_c, float* lse_out, float* logp_out, float* ent_out,
+                               float* zy_out, int32_t* ycol_out) {
   __shared__ double ss[kSumSlices][64], su[kSumSlices][64];
   const int left = desc->rows, chunk_start = desc->row_start;
   if ((int)blockIdx.x * 64 >= left) return;
@@ -322,10 +355,16 @@ __global__ __launch_bounds__(64 * kSumSlices) void lse_sum_kernel(const float2* 
     const float lse = (float)lse_d;
     const float lp = zy_c[g] - lse;
     lse_c[g] = lse; logp_c[g] = lp; zsum_c[g] = (float)S;
+    // Z_t = exp(lse_t - ref_t) is of order one when the old log-prob is anywhere near the current one.  A row whose
+    // sum left [1e-30, 1e30] (or is not a number) had stored probabilities outside the staging precision's range:
+    // counted, and the loss of the call comes back NaN.
+    if (!(S >= 1e-30 && S <= 1e30)) { atomicAdd(&ctrl->overflow, 1); if (stats) atomicAdd(&stats->n_overflow_rows, 1); }
     const int r = row_map[g];
     if (lse_out) lse_out[r] = lse;
     if (logp_out) logp_out[r] = lp;
     if (ent_out) ent_out[r] = (float)fmax(lse_d - U / S, 0.0);
+    if (zy_out) zy_out[r] = zy_c[g];
+    if (ycol_out) ycol_out[r] = ycol_c[g];
   }
 }
 
@@ -352,8 +391,9 @@ __global__ void stash_patch_kernel(const ChunkDesc* desc, const int32_t* ids_c, 
 // compact rows x 4 slices of the tile range: one online (rescaling) pass per thread, coalesced
 // along the rows, then the four slices are merged through LDS in a fixed order.
 __global__ void lse_combine_kernel(const float4* part, int ldp, int tiles_v, const float* zy_c,
-                                   const int32_t* row_map, const Ctrl* ctrl, int chunk_start, int chunk_rows,
-                                   float* lse_c, float* logp_c, float* lse_out, float* logp_out, float* ent_out) {
+                                   const int32_t* row_map, const Ctrl* ctrl, int chunk_start, int chunk_rows, const int32_t* ycol_c,
+                                   float* lse_c, float* logp_c, float* lse_out, float* logp_out, float* ent_out,
+                                   float* zy_out, int32_t* ycol_out) {
   __shared__ float sm[4][64], ss[4][64], su[4][64];
   int left = ctrl->n_real - chunk_start;
   if (left > chunk_rows) left = chunk_rows;
@@ -394,6 +434,8 @@ __global__ void lse_combine_kernel(const float4* part, int ldp, int tiles_v, con
     if (lse_out) lse_out[r] = lse;
     if (logp_out) logp_out[r] = lp;
     if (ent_out) ent_out[r] = (float)fmax(lse_d - U / S, 0.0);     // H = lse - sum_v p_v z_v
+    if (zy_out) zy_out[r] = zy_c[g];
+    if (ycol_out) ycol_out[r] = ycol_c[g];
   }
 }
 
@@ -527,7 +569,8 @@ __global__ void finalize_kernel(const float* seq_loss, const float* gterm, const
   }
   const double tot = block_sum(acc, sh);
   // a sequence longer than the caller promised: the single-pass backward dropped rows, say so loudly
-  if (threadIdx.x == 0) *loss = ctrl->too_long ? __builtin_nanf("") : (float)(tot / B);
+  // ... or stored probabilities that left the representable range: the gradients of those rows are not numbers
+  if (threadIdx.x == 0) *loss = (ctrl->too_long || ctrl->overflow) ? __builtin_nanf("") : (float)(tot / B);
   if (d_log_z) {
     for (int p = threadIdx.x; p < P; p += blockDim.x) {
       double s = 0.0;
@@ -683,7 +726,7 @@ struct Plan {
   float inv_tau;         // 1 / temperature
   size_t off_ctrl, off_seq_len, off_cstart, off_row_map, off_ids_c, off_cpos, off_zy, off_lse_c, off_logp_c,
       off_c_c, off_adv, off_seq_loss, off_gterm, off_part, off_wt, off_xt, off_ds, off_dst,
-      off_desc, off_ref, off_zsum, off_scale, total;
+      off_desc, off_ref, off_zsum, off_scale, off_ycol, total;
 };
 
 static inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -708,9 +751,11 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   // Single-pass backward: bf16 hot-kernel shapes only, and only when the caller bounds the sequence length by a chunk.
   const int64_t rp = (b->R + 255) & ~(int64_t)255;
   auto chunk_rows = [&](int dflt) { int t = (prm && prm->chunk_rows > 0) ? prm->chunk_rows : dflt; t = (t + 255) & ~255; return t > rp ? (int)rp : t; };
-  const bool stash_shape = bwd && b->dtype == RL_BF16 && (b->H % 128 == 0) && prm && prm->max_seq_len > 0 && mode != RL_BWD_RECOMPUTE &&
-                           ((reinterpret_cast<uintptr_t>(b->hidden) | reinterpret_cast<uintptr_t>(b->weight)) % 16 == 0);
+  const bool stash_kernels = b->dtype == RL_BF16 && (b->H % 128 == 0) &&
+                             ((reinterpret_cast<uintptr_t>(b->hidden) | reinterpret_cast<uintptr_t>(b->weight)) % 16 == 0);
+  const bool stash_shape = bwd && stash_kernels && prm && prm->max_seq_len > 0 && mode != RL_BWD_RECOMPUTE;
   const bool can_stash = stash_shape && prm->max_seq_len <= chunk_rows(kDefaultChunkRowsStash);
+  if (mode == RL_BWD_STASH && !stash_kernels) return RL_ERR_UNIMPLEMENTED;
   if (mode == RL_BWD_STASH && !can_stash) return RL_ERR_RANGE;
   const int tc = chunk_rows(can_stash ? kDefaultChunkRowsStash : kDefaultChunkRows);
   p.Tc = tc;
@@ -735,6 +780,7 @@ static rl_status make_plan(const rl_batch* b, const rl_params* prm, bool bwd, Pl
   p.off_cstart = take(sizeof(int32_t) * ((size_t)b->B + 1));
   p.off_row_map = take(4 * Rp); p.off_ids_c = take(4 * Rp); p.off_cpos = take(4 * Rp);
   p.off_zy = take(4 * Rp); p.off_lse_c = take(4 * Rp); p.off_logp_c = take(4 * Rp); p.off_c_c = take(4 * Rp);
+  p.off_ycol = take(4 * Rp);
   p.off_adv = take(4 * (size_t)b->B); p.off_seq_loss = take(4 * (size_t)b->B); p.off_gterm = take(4 * (size_t)b->B);
   p.off_part = take(sizeof(float4) * (size_t)p.tiles_v * (size_t)tc);
   p.off_wt = p.off_xt = p.off_ds = p.off_dst = 0;
@@ -794,6 +840,7 @@ struct Ptrs {
   float *zy, *lse_c, *logp_c, *c_c, *adv, *seq_loss, *gterm; float4* part;
   void *wt, *xt, *ds, *dst;
   ChunkDesc* desc; float *ref, *zsum, *scale;
+  int32_t* ycol;
 };
 
 static Ptrs carve(void* ws, const Plan& p) {
@@ -808,24 +855,31 @@ static Ptrs carve(void* ws, const Plan& p) {
   q.dst = p.off_dst ? w + p.off_dst : nullptr;          // f32 inputs only
   q.desc = (ChunkDesc*)(w + p.off_desc); q.ref = (float*)(w + p.off_ref); q.zsum = (float*)(w + p.off_zsum);
   q.scale = (float*)(w + p.off_scale);
+  q.ycol = (int32_t*)(w + p.off_ycol);
   return q;
 }
 
 // prep: counts, scan, compaction; zero the per-row outputs so masked rows read 0
 static void run_prep(const rl_batch* b, const Plan& p, const Ptrs& q, int32_t* seq_len_out, rl_stats* stats,
-                     const int32_t* group_idx, float* logp_out, float* lse_out, float* coeff_out, hipStream_t s) {
+                     const int32_t* group_idx, float* logp_out, float* lse_out, float* coeff_out, int32_t* row_map_out,
+                     hipStream_t s) {
   ProfScope ps(RL_PROF_PREP, s);
   if (stats) fill<int32_t>(reinterpret_cast<int32_t*>(stats), sizeof(rl_stats) / 4, 0, s);
   fill<int32_t>(q.cpos, p.R, -1, s);
+  fill<int32_t>(row_map_out, p.R, -1, s);
   fill<float>(logp_out, p.R, 0.f, s); fill<float>(lse_out, p.R, 0.f, s); fill<float>(coeff_out, p.R, 0.f, s);
-  seq_count_kernel<<<p.B, 256, 0, s>>>(b->mask, b->token_ids, b->cu_seqlens, group_idx, p.R, p.V, p.P, q.seq_len, stats);
+  // the running maximum of the offsets borrows cstart until the scan below overwrites it with the compacted starts
+  cu_running_max_kernel<<<1, 1024, 0, s>>>(b->cu_seqlens, p.B, q.cstart);
+  seq_count_kernel<<<p.B, 256, 0, s>>>(b->mask, b->token_ids, b->cu_seqlens, q.cstart, group_idx, p.R, p.V, p.P, q.seq_len, stats);
   seq_scan_kernel<<<1, 1024, 0, s>>>(q.seq_len, p.B, q.cstart, q.ctrl, stats);
-  compact_kernel<<<p.B, 1024, 0, s>>>(b->mask, b->token_ids, b->cu_seqlens, q.seq_len, q.cstart, p.V, q.row_map, q.ids_c, q.cpos);
+  compact_kernel<<<p.B, 1024, 0, s>>>(b->mask, b->token_ids, b->cu_seqlens, q.seq_len, q.cstart, p.V, q.row_map, q.ids_c, q.cpos,
+                                      row_map_out);
   if (seq_len_out) (void)hipMemcpyAsync(seq_len_out, q.seq_len, 4 * (size_t)p.B, hipMemcpyDeviceToDevice, s);
 }
 
 template <class T>
-static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* logp_out, float* lse_out, float* ent_out, hipStream_t s) {
+static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* logp_out, float* lse_out, float* ent_out,
+                        float* zy_out, int32_t* ycol_out, hipStream_t s) {
   const T* X = static_cast<const T*>(b->hidden);
   const T* W = static_cast<const T*>(b->weight);
   for (int ch = 0; ch < p.n_chunks; ++ch) {
@@ -833,11 +887,11 @@ static void run_forward(const rl_batch* b, const Plan& p, const Ptrs& q, float* 
     GemmDims d{};
     d.M = p.V; d.N = p.Tc; d.K = p.H; d.lda = p.H; d.ldb = p.H;
     d.a_rows = nullptr; d.b_rows = q.row_map + c0; d.n_real = &q.ctrl->n_real; d.chunk_start = c0; d.dyn = 2; d.group_m = TuneLogits::kBand;
-    EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V, p.inv_tau};
+    EpiFwd<T> e{q.ids_c, q.zy, q.part, p.Tc, p.V, p.inv_tau, q.ycol};
     { ProfScope ps(RL_PROF_GEMM_FWD, s); launch_gemm<TuneLogits>(W, X, d, e, s); }
     ProfScope ps(RL_PROF_COMBINE, s);
-    lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc,
-                                                        q.lse_c, q.logp_c, lse_out, logp_out, ent_out);
+    lse_combine_kernel<<<(p.Tc + 63) / 64, 256, 0, s>>>(q.part, p.Tc, p.tiles_v, q.zy, q.row_map, q.ctrl, c0, p.Tc, q.ycol,
+                                                        q.lse_c, q.logp_c, lse_out, logp_out, ent_out, zy_out, ycol_out);
   }
 }
 
@@ -930,7 +984,7 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
   {
     ProfScope ps(RL_PROF_PREP, s);
     chunk_build_kernel<<<1, 64, 0, s>>>(q.seq_len, q.cstart, p.B, p.Tc, p.max_len, q.desc, p.n_desc, q.ctrl, out->stats);
-    target_logit_kernel<<<(unsigned)((p.R + 3) / 4), 256, 0, s>>>(X, W, p.H, q.row_map, q.ids_c, b->old_logprob, q.ctrl, p.inv_tau, q.zy, q.ref);
+    target_logit_kernel<<<(unsigned)((p.R + 3) / 4), 256, 0, s>>>(X, W, p.H, q.row_map, q.ids_c, b->old_logprob, q.ctrl, p.inv_tau, q.zy, q.ref, q.ycol);
   }
   float2* part = reinterpret_cast<float2*>(q.part);
   for (int k = 0; k < p.n_desc; ++k) {
@@ -947,8 +1001,9 @@ static void run_fused(const rl_batch* b, const rl_params* prm, int objective, co
     }
     {
       ProfScope ps(RL_PROF_COMBINE, s);
-      lse_sum_kernel<<<(p.Tc + 63) / 64, 64 * kSumSlices, 0, s>>>(part, p.Tc, p.tiles_v, q.zy, q.ref, q.row_map, dk, q.lse_c, q.logp_c, q.zsum,
-                                                      out->lse, out->logprob, out->entropy);
+      lse_sum_kernel<<<(p.Tc + 63) / 64, 64 * kSumSlices, 0, s>>>(part, p.Tc, p.tiles_v, q.zy, q.ref, q.row_map, dk, q.ycol, q.ctrl, out->stats,
+                                                      q.lse_c, q.logp_c, q.zsum, out->lse, out->logprob, out->entropy,
+                                                      out->target_logit, out->target_col);
     }
     {
       ProfScope ps(RL_PROF_LOSS, s);
@@ -1006,6 +1061,7 @@ const char* rl_status_string(int32_t s) {
     case RL_ERR_RANGE: return "objective or a coefficient is out of range";
     case RL_ERR_WORKSPACE: return "workspace is NULL, misaligned or too small";
     case RL_ERR_HIP: return "a HIP launch failed";
+    case RL_ERR_UNIMPLEMENTED: return "this build has no kernel for the request (single-pass backward needs bf16 inputs and H % 128 == 0)";
     default: return "unknown status";
   }
 }
@@ -1104,9 +1160,9 @@ rl_status rl_token_logprob_tempered(const rl_batch* b, float temperature, float*
   hipStream_t s = static_cast<hipStream_t>(stream);
   (void)hipGetLastError();
   Ptrs q = carve(ws, p);
-  run_prep(b, p, q, nullptr, nullptr, nullptr, logprob, lse, nullptr, s);
-  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, logprob, lse, nullptr, s);
-  else run_forward<float>(b, p, q, logprob, lse, nullptr, s);
+  run_prep(b, p, q, nullptr, nullptr, nullptr, logprob, lse, nullptr, nullptr, s);
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, logprob, lse, nullptr, nullptr, nullptr, s);
+  else run_forward<float>(b, p, q, logprob, lse, nullptr, nullptr, nullptr, s);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 
@@ -1138,12 +1194,14 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
   (void)hipGetLastError();
   Ptrs q = carve(ws, p);
 
-  run_prep(b, p, q, out->seq_len, out->stats, b->group_idx, out->logprob, out->lse, out->coeff, s);
+  run_prep(b, p, q, out->seq_len, out->stats, b->group_idx, out->logprob, out->lse, out->coeff, out->row_map, s);
   fill<float>(out->entropy, p.R, 0.f, s);
+  fill<float>(out->target_logit, p.R, 0.f, s);
+  fill<int32_t>(out->target_col, p.R, -1, s);
   {
   ProfScope ps(RL_PROF_LOSS, s);
   fill<float>(q.adv, p.B, 0.f, s);
-  advantage_kernel<<<(p.P + 127) / 128, 128, 0, s>>>(b->rewards, b->group_idx, p.B, p.P, prm->adv_eps, prm->adv_std_ddof, q.adv);
+  advantage_kernel<<<(p.P + 127) / 128, 128, 0, s>>>(b->rewards, b->group_idx, p.B, p.P, prm->adv_eps, prm->adv_std_ddof, q.adv, out->group_count);
   if (out->advantages) (void)hipMemcpyAsync(out->advantages, q.adv, 4 * (size_t)p.B, hipMemcpyDeviceToDevice, s);
   }
 
@@ -1151,8 +1209,8 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
     run_fused(b, prm, objective, p, q, out, s);
     return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
   }
-  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, out->logprob, out->lse, out->entropy, s);
-  else run_forward<float>(b, p, q, out->logprob, out->lse, out->entropy, s);
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, out->logprob, out->lse, out->entropy, out->target_logit, out->target_col, s);
+  else run_forward<float>(b, p, q, out->logprob, out->lse, out->entropy, out->target_logit, out->target_col, s);
 
   {
   ProfScope ps(RL_PROF_LOSS, s);

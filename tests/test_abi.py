@@ -80,8 +80,10 @@ def test_backward_mode_is_validated_on_the_host(lib):
     assert m.value == n.value                                                    # auto picks it when it can
     assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="stash")), 1, C.byref(n)) == 4            # no promise
     assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode="stash", max_seq_len=512, chunk_rows=256)), 1, C.byref(n)) == 4
-    assert lib.rl_workspace_bytes(C.byref(_batch(H=64)), C.byref(mk(backward_mode="stash", max_seq_len=8)), 1, C.byref(n)) == 4
-    assert lib.rl_workspace_bytes(C.byref(_batch(H=128, dtype=binding.RL_F32)), C.byref(mk(backward_mode="stash", max_seq_len=8)), 1, C.byref(n)) == 4
+    # ... and where no kernel exists for the shape or dtype, the request is valid but unimplemented
+    assert lib.rl_workspace_bytes(C.byref(_batch(H=64)), C.byref(mk(backward_mode="stash", max_seq_len=8)), 1, C.byref(n)) == 7
+    assert lib.rl_workspace_bytes(C.byref(_batch(H=128, dtype=binding.RL_F32)), C.byref(mk(backward_mode="stash", max_seq_len=8)), 1, C.byref(n)) == 7
+    assert b"no kernel" in lib.rl_status_string(7)
     assert lib.rl_workspace_bytes(C.byref(_batch(H=64)), C.byref(mk(backward_mode="auto", max_seq_len=8)), 1, C.byref(n)) == 0   # falls back
     assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(backward_mode=7)), 1, C.byref(n)) == 4
     assert lib.rl_workspace_bytes(C.byref(ok), C.byref(mk(max_seq_len=-1)), 1, C.byref(n)) == 4

@@ -1,12 +1,12 @@
 """GPU parity of the residual-VQ encode against its float64 oracle, through the C ABI.
 
-Codes are integers, so the bar is exact equality - with one proviso the method itself carries: the nearest entry is
-decided by floating-point distances, the oracle decides in float64 from the stored bf16 values and the kernel in
-float32 (MFMA accumulation), so two entries whose distances agree to ~1e-7 relative may swap, after which the two
-paths legitimately diverge.  What is unique is compared exactly (every code row on which both agree, which must be
-almost all of them, and the residual given the codes, bit for bit); the rest is checked for validity decision by
-decision by the oracle, walking the kernel's own path: each chosen entry must be a nearest entry to within 2e-6 of
-the distance scale."""
+Codes are integers, so the bar is exact equality, and on the seeded inputs of these tests it is asserted: every code
+and every residual bit equals the float64 oracle's (no decision differs).  The method carries one proviso that the
+tests also cover: the nearest entry is decided by floating-point distances, the oracle decides in float64 from the
+stored bf16 values and the kernel in float32 (MFMA accumulation), so on other inputs two entries whose distances agree
+to ~1e-7 relative could swap.  Independently of the exact comparison, the oracle therefore walks the kernel's own path
+decision by decision: each chosen entry must be a nearest entry to within 2e-6 of the distance scale, and the residual
+must follow from the kernel's own codes bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -21,7 +21,7 @@ def _bits(t):
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
 
 
-def _compare(x, cb, codes, res, min_agree):
+def _compare(x, cb, codes, res):
     G = x.shape[0]
     n_rows = n_same = n_diff_dec = 0
     for g in range(G):
@@ -41,7 +41,8 @@ def _compare(x, cb, codes, res, min_agree):
         for i in range(C.shape[0]):
             rb = rvq.bf16_round_bits(rvq.widen(rb.view(np.int16)) - C[i, got[:, i]])
         np.testing.assert_array_equal(_bits(res[g]), rb)
-    assert n_same >= min_agree * n_rows, (n_same, n_rows)
+    # pinned on these seeds: every row equal, no decision other than the float64 argmin
+    assert n_same == n_rows and n_diff_dec == 0, (n_same, n_rows, n_diff_dec)
     return n_same, n_rows, n_diff_dec
 
 
@@ -53,7 +54,7 @@ def test_rvq_encode_matches_the_oracle(G, L, N, S):
     codes, res = binding.rl_rvq_encode(x, cb)
     torch.cuda.synchronize()
     assert int(codes.min()) >= 0 and int(codes.max()) < S
-    print(_compare(x, cb, codes, res, 0.995))
+    print(_compare(x, cb, codes, res))
 
 
 def test_rvq_encode_key_cache_shape_sampled():
@@ -64,7 +65,7 @@ def test_rvq_encode_key_cache_shape_sampled():
     torch.cuda.synchronize()
     pick = torch.from_numpy(np.random.default_rng(1).choice(1024, 96, replace=False)).cuda()
     for g in range(2):
-        n_same, n_rows, nd = _compare(x[g:g + 1, pick], cb[g:g + 1], codes[g:g + 1, pick], res[g:g + 1, pick], 0.9)
+        n_same, n_rows, nd = _compare(x[g:g + 1, pick], cb[g:g + 1], codes[g:g + 1, pick], res[g:g + 1, pick])
         print("group", g, "rows equal", n_same, "of", n_rows, "decisions differing from the float64 argmin", nd)
     # properties at full size: the residual norm shrinks (random codebooks at matched scale), codes in range
     r0 = x.float().pow(2).sum(-1).mean().item(); r1 = res.float().pow(2).sum(-1).mean().item()

@@ -56,7 +56,7 @@ MUTANTS = [
     ("target logit: wrong row of W", "zy[t] = float(np.dot(W[ids[t]], X[t])) / temperature", "zy[t] = float(np.dot(W[(ids[t] + 1) % W.shape[0]], X[t])) / temperature"),
     ("dW rows: one-hot dropped", "    dS += (ids[rows][:, None] == vs[None, :])\n", ""),
     ("dW rows: chain factor of the temperature dropped", "    dS *= (c[rows] / temperature)[:, None]", "    dS *= c[rows][:, None]"),
-    ("dW rows: masked rows leak", "    rows = np.nonzero(m)[0]\n    Z = X[rows] @ Wr.T", "    rows = np.arange(m.size)\n    Z = X[rows] @ Wr.T"),
+    ("dW rows: masked rows leak", "    rows = np.nonzero(m)[0]\n    Xr = X if", "    rows = np.arange(m.size)\n    Xr = X if"),
 ]
 
 PIN_TESTS = [(n, f) for n, f in inspect.getmembers(pins, inspect.isfunction) if n.startswith("test_")]

@@ -26,7 +26,8 @@ def test_compression_ratio_matches_the_values_the_paper_prints():
             continue
         name, nk, nv, sk, sv, d, want = line.split()
         got = rvq.compression_ratio(int(nk), int(sk), int(nv), int(sv), int(d), int(d))
-        assert round(got, 1) == float(want), (name, got)
+        # printed to one decimal; the table rounds the exact tie 81.25 up to 81.3, so compare within half a unit of that decimal
+        assert abs(got - float(want)) <= 0.05 + 1e-9, (name, got)
     assert rvq.compression_ratio(16, 2 ** 16, 16, 2 ** 16, 16, 16) == 0.0          # 16 codes of 16 bits for 16 values: nothing saved
 
 
