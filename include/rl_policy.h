@@ -179,6 +179,18 @@ rl_status rl_token_logprob(const rl_batch* batch, float* logprob, float* lse,
 rl_status rl_token_logprob_tempered(const rl_batch* batch, float temperature, float* logprob, float* lse,
                                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate or hand over a workspace (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): rl_token_logprob_tempered with its workspace in a static device array of
+ * RL_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until the process ends.  The call itself allocates
+ * nothing (no hipMalloc / hipFree, no allocating library routine) and clears what it needs itself; the caller still
+ * passes inputs and outputs.  The chunk size is chosen so that the plan fits the array; a batch whose plan does not
+ * fit even with 256-row chunks (about 32 bytes per row plus 16 bytes x ceil(V / 256) x 256) is rejected with
+ * RL_ERR_WORKSPACE before anything is launched.  All calls on one GPU share that GPU's array: calls that overlap on one
+ * GPU (two streams, two threads) race; serialise them.  The first call on a device looks the array's address up
+ * (not capturable: make one call before capturing a graph).  Results are bit-identical to rl_token_logprob_tempered. */
+#define RL_STATIC_SCRATCH_BYTES (32u << 20)
+rl_status rl_token_logprob_static(const rl_batch* batch, float temperature, float* logprob, float* lse, void* stream);
+
 /* The whole path: log-prob, per-sequence length-normalised sums, group advantage, loss and
  * per-token coefficient, and (if d_hidden and d_weight are given) the backward pass. */
 rl_status rl_policy_loss_fwd_bwd(const rl_batch* batch, const rl_params* params,

@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         L.rl_token_logprob.restype = C.c_int
         L.rl_token_logprob_tempered.argtypes = [C.POINTER(rl_batch), C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.rl_token_logprob_tempered.restype = C.c_int
+        L.rl_token_logprob_static.argtypes = [C.POINTER(rl_batch), C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.rl_token_logprob_static.restype = C.c_int
         L.rl_policy_loss_fwd_bwd.argtypes = [C.POINTER(rl_batch), C.POINTER(rl_params), C.c_int32,
                                              C.POINTER(rl_outputs), C.c_void_p, C.c_size_t, C.c_void_p]
         L.rl_policy_loss_fwd_bwd.restype = C.c_int
@@ -193,6 +195,14 @@ def rl_token_logprob(hidden, weight, token_ids, mask, cu_seqlens=None, workspace
 def rl_token_logprob_tempered(hidden, weight, token_ids, mask, temperature, cu_seqlens=None, workspace=None):
     """The same under softmax(W x / temperature)."""
     return _token_logprob(hidden, weight, token_ids, mask, cu_seqlens, workspace, float(temperature))
+
+
+def rl_token_logprob_static(hidden, weight, token_ids, mask, cu_seqlens, logprob, lse, temperature=1.0):
+    """The scoring call that allocates nothing: its workspace is a static device array of the library (batches beyond
+    its size are refused).  The caller passes everything, outputs logprob[R] / lse[R] (float32) included."""
+    b = make_batch(hidden, weight, token_ids, mask, cu_seqlens)
+    _check(lib().rl_token_logprob_static(C.byref(b), float(temperature), _ptr(logprob, torch.float32, b.R, "logprob"),
+                                         _ptr(lse, torch.float32, b.R, "lse"), _stream_handle()))
 
 
 def _token_logprob(hidden, weight, token_ids, mask, cu_seqlens, workspace, temperature):

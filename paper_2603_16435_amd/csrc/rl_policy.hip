@@ -16,6 +16,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
 #include <utility>
 #include <vector>
 
@@ -1224,6 +1225,57 @@ rl_status rl_policy_loss_fwd_bwd(const rl_batch* b, const rl_params* prm, int32_
     if (p.dtype == RL_BF16) run_backward<bf16_t>(b, p, q, out->d_hidden, out->d_weight, s);
     else run_backward<float>(b, p, q, out->d_hidden, out->d_weight, s);
   }
+  return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
+}
+
+// ------------------------------------------------------------------ scoring call that allocates nothing
+// The forward-only call with its workspace in a file-scope device array instead of a caller's buffer.  Every GPU the
+// library runs on holds its own copy of the array at its own address; the host-side name of the array is only a handle
+// for hipGetSymbolAddress, never a device address, so the address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[RL_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static rl_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RL_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RL_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return RL_OK;
+}
+
+rl_status rl_token_logprob_static(const rl_batch* b, float temperature, float* logprob, float* lse, void* stream) {
+  if (!b) return RL_ERR_NULL;
+  if (!b->hidden || !b->weight || !b->token_ids || !b->mask || !b->cu_seqlens) return RL_ERR_NULL;
+  if (!logprob && !lse) return RL_ERR_NULL;
+  if (!(temperature > 0.f) || !(temperature <= 3.0e38f)) return RL_ERR_RANGE;
+  // the largest chunk (a power of two times 256 rows) whose plan fits the array; none fits: the batch is beyond the limit
+  Plan p;
+  bool fits = false;
+  for (int tc = kDefaultChunkRows; tc >= 256 && !fits; tc >>= 1) {
+    rl_params prm{};
+    prm.chunk_rows = tc;
+    const rl_status st = make_plan(b, &prm, false, p);
+    if (st != RL_OK) return st;
+    fits = p.total <= (size_t)RL_STATIC_SCRATCH_BYTES;
+  }
+  if (!fits) return RL_ERR_WORKSPACE;
+  p.inv_tau = 1.f / temperature;
+  void* ws = nullptr;
+  const rl_status st = static_scratch(&ws);
+  if (st != RL_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  Ptrs q = carve(ws, p);
+  run_prep(b, p, q, nullptr, nullptr, nullptr, logprob, lse, nullptr, nullptr, s);
+  if (p.dtype == RL_BF16) run_forward<bf16_t>(b, p, q, logprob, lse, nullptr, nullptr, nullptr, s);
+  else run_forward<float>(b, p, q, logprob, lse, nullptr, nullptr, nullptr, s);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 
