@@ -109,6 +109,9 @@ def lib() -> C.CDLL:
         L.rl_rvq_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p]
         L.rl_rvq_encode.restype = C.c_int
+        L.rl_rvq_encode_counted.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.rl_rvq_encode_counted.restype = C.c_int
         L.rl_version.restype = C.c_int32
         L.rl_default_chunk_rows.restype = C.c_int32
         L.rl_default_chunk_rows_single_pass.restype = C.c_int32
@@ -384,8 +387,10 @@ def rl_rvq_codebook_norms(codebooks):
     return norms
 
 
-def rl_rvq_encode(vectors, codebooks, norms=None, want_residual=True):
-    """codes [G, L, N] int32 (and the residual [G, L, D] bfloat16) of vectors [G, L, D] under codebooks [G, N, S, D]."""
+def rl_rvq_encode(vectors, codebooks, norms=None, want_residual=True, count_exact=None):
+    """codes [G, L, N] int32 (and the residual [G, L, D] bfloat16) of vectors [G, L, D] under codebooks [G, N, S, D].
+    count_exact: optional int32[1] device tensor that the diagnostic entry point adds the number of decisions to that
+    were re-evaluated exactly in float64."""
     G, L, D = vectors.shape
     _, N, S, _ = codebooks.shape
     assert vectors.dtype == torch.bfloat16 and vectors.is_contiguous() and codebooks.shape[0] == G and codebooks.shape[3] == D
@@ -393,6 +398,11 @@ def rl_rvq_encode(vectors, codebooks, norms=None, want_residual=True):
         norms = rl_rvq_codebook_norms(codebooks)
     codes = torch.empty(G, L, N, dtype=torch.int32, device=vectors.device)
     res = torch.empty_like(vectors) if want_residual else None
+    if count_exact is not None:
+        _check(lib().rl_rvq_encode_counted(vectors.data_ptr(), codebooks.data_ptr(), norms.data_ptr(), G, L, D, N, S, codes.data_ptr(),
+                                           res.data_ptr() if want_residual else None, _ptr(count_exact, torch.int32, 1, "count_exact"),
+                                           _stream_handle()))
+        return codes, res
     _check(lib().rl_rvq_encode(vectors.data_ptr(), codebooks.data_ptr(), norms.data_ptr(), G, L, D, N, S, codes.data_ptr(),
                                res.data_ptr() if want_residual else None, _stream_handle()))
     return codes, res

@@ -1356,6 +1356,11 @@ rl_status rl_rvq_codebook_norms(const void* codebooks, int32_t G, int32_t N, int
 
 rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,
                         int32_t N, int32_t S, int32_t* codes, void* residual, void* stream) {
+  return rl_rvq_encode_counted(vectors, codebooks, norms, G, L, D, N, S, codes, residual, nullptr, stream);
+}
+
+rl_status rl_rvq_encode_counted(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,
+                                int32_t N, int32_t S, int32_t* codes, void* residual, int32_t* n_exact, void* stream) {
   if (!vectors || !codebooks || !norms || !codes) return RL_ERR_NULL;
   rl_status st = rvq_check(G, L, D, N, S);
   if (st != RL_OK) return st;
@@ -1363,7 +1368,7 @@ rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float*
   (void)hipGetLastError();
   dim3 grid((unsigned)((L + kRvqVecs - 1) / kRvqVecs), G);
   rvq_encode_kernel<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const bf16_t*>(vectors), static_cast<const bf16_t*>(codebooks), norms,
-                                                                       (int)L, N, S, codes, static_cast<bf16_t*>(residual));
+                                                                       (int)L, N, S, codes, static_cast<bf16_t*>(residual), n_exact);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 

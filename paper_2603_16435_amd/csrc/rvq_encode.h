@@ -6,12 +6,24 @@
 // with the lowest index winning ties and the running residual kept in the cache's 16-bit storage precision.
 //
 // Mapping to the hardware.  A workgroup of four wavefronts takes 256 vectors of one codebook group and walks all N
-// stages with the residuals in registers (already in MFMA operand layout: a lane holds row l%16, 8 consecutive k).
-// A stage's codebook (S x 128 bf16) streams through LDS in chunks of 64 entries (16 KiB, double-buffered, fetched
-// into registers one chunk ahead); per chunk a wavefront does 64 v_mfma_f32_16x16x32_bf16 (64 vectors x 64 entries
-// x K = 128) and folds the 64 scores of each lane into a running (best score, index) pair per row.  Stage end: the
-// 16 lanes that share rows merge their pairs (value first, then lower index), the winners go through LDS to the
-// lanes that own those rows in operand layout, which fetch the chosen entry (16-byte gathers) and update the residual.
+// stages with the residuals in registers, already in MFMA operand layout (a lane holds vector l%16 of a block of 16,
+// 8 consecutive k).  A stage's codebook (S x 128 bf16) streams through LDS in chunks of 64 entries (16 KiB, two stages,
+// filled by global -> LDS loads one chunk ahead).  The scores are computed ENTRY-major: A = 16 entries, B = 16 vectors,
+// so that in the accumulator layout a lane owns ONE vector per block and four entries of it.  A lane then keeps one
+// running (best score, second-best score, index) triple per vector block - four triples in all, whatever S is - updated
+// with four vector operations per score (compare, median-of-three, select, max; the index operand is uniform over the
+// wavefront), and at the end of a stage the four lanes that share a vector merge their triples with two exchanges; the
+// winner's index is then already in the lanes that hold that vector's residual.  The accumulators of a block of 16
+// entries start at -|c|^2/2 through the MFMA's C operand, and the blocks of a chunk are software-pipelined: the updates
+// of block c run under the MFMAs of block c+1.
+//
+// Exactness.  The scores come out of f32 accumulation, the definition is exact.  Products of bf16 values are exact in
+// f32, so a score differs from its exact value by at most g (|r| |c| + |c|^2 / 2) with g = 2^-16 (256 roundings of
+// relative size 2^-24 would be needed to exceed it; a score goes through about 160).  If the best f32 score of a vector
+// leads the second best by more than 2 g (|r| c_max + c_max^2 / 2), the winner is the exact arg-max.  Otherwise
+// (about one decision in a thousand, and always for duplicated entries) the wavefront re-evaluates that vector against
+// all S entries in float64 straight from the definition, sum_d (r_d - c_d)^2, smallest distance first, lowest index on
+// ties.  The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.
 // LDS layout: entry e at 256 e, its 16-byte piece p at slot p ^ (e & 15): fragment reads are conflict-free.
 #pragma once
 #include "gemm_nt.h"
@@ -21,6 +33,7 @@ namespace rlk {
 constexpr int kRvqD = 128;          // head dimension the kernel is written for
 constexpr int kRvqChunk = 64;       // codebook entries per LDS chunk
 constexpr int kRvqVecs = 256;       // vectors per workgroup
+constexpr float kRvqGamma2 = 3.0517578125e-05f;   // 2 g = 2^-15: twice the bound on the relative error of an f32 score
 
 // squared norms of the entries, f32 (products of bf16 are exact in f32; summed in index order)
 __global__ void rvq_norms_kernel(const bf16_t* cb, int64_t entries, float* cn) {
@@ -52,14 +65,69 @@ __device__ inline u32x4_t rvq_sub_bf16(const u32x4_t& r, const u32x4_t& c) {   /
   return o;
 }
 
+__device__ inline float rvq_sumsq(const u32x4_t& r, float acc) {               // acc + sum of squares of eight packed bf16
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = __uint_as_float(r[j] << 16), hi = __uint_as_float(r[j] & 0xffff0000u);
+    acc = fmaf(lo, lo, acc); acc = fmaf(hi, hi, acc);
+  }
+  return acc;
+}
+
+// ---- exact decisions for the vectors whose float32 lead was inside the rounding margin.  Done by the whole workgroup at
+// the end of a stage, up to 16 such vectors at a time (there is one in every second or third stage of a workgroup):
+//  1. The vectors become the 16 columns of an MFMA B operand and the float32 scores r . c - |c|^2 / 2 of all S entries
+//     are recomputed on the matrix cores, a quarter of the entries per wavefront, fetched straight from memory in
+//     operand layout, four groups of 16 entries in flight.
+//  2. An entry within the vector's margin (twice the bound on a score's error) of the largest score could be the exact
+//     arg-max; no other entry can.  The largest recomputed score is at least the main pass's best score minus the margin
+//     (both are within the error bound of the same exact value), and no smaller than any running maximum; so every such
+//     entry is within the margin of max(that floor, the lane's running maximum) when it arrives.  Those are listed per
+//     vector (two or three), and the list is then cut down against the final maximum.
+//  3. The survivors are evaluated from the definition in float64, sum_d (r_d - c_d)^2 from the stored bf16 values; the
+//     smallest distance wins, the lowest index on ties.
+constexpr int kRvqSlots = 16;       // vectors resolved per round
+constexpr int kRvqCand = 32;        // listed entries per vector; more (that many scores within twice the margin): all S evaluated
+struct RvqResolveLds {
+  u32x4_t bits[kRvqSlots][kRvqD / 8];     // the vectors as stored: 16 pieces of eight bf16 each
+  float margin[kRvqSlots];
+  float best[kRvqSlots];                  // the main pass's best score
+  int owner[kRvqSlots];                   // 64 * wavefront + 16 * vector block + vector: who gets the answer
+  int count[kRvqSlots];                   // entries listed (may run past kRvqCand: then the list is not used)
+  int cand[kRvqSlots][kRvqCand];
+  float cscore[kRvqSlots][kRvqCand];
+  float top[kRvqSlots][16];               // running maxima at the end of the pass, per wavefront and lane group
+  int result[kRvqSlots];
+  int n;                                  // vectors that asked for a slot this round (may exceed kRvqSlots: the rest go next round)
+};
+
+// Squared distance of the vector in slot j to one entry, straight from the definition in float64: lane l takes components
+// 2 l and 2 l + 1, the 64 partial sums are added in a fixed tree (the same for every entry, so equal entries give equal sums).
+__device__ __attribute__((always_inline)) inline double rvq_exact_distance(const RvqResolveLds& q, int j, const bf16_t* stage_cb, int ent, int lane) {
+  const unsigned w = *reinterpret_cast<const unsigned*>(stage_cb + (int64_t)ent * kRvqD + 2 * lane);
+  const unsigned r = reinterpret_cast<const unsigned*>(&q.bits[j][0])[lane];
+  const double d0 = (double)__uint_as_float(r << 16) - (double)__uint_as_float(w << 16);
+  const double d1 = (double)__uint_as_float(r & 0xffff0000u) - (double)__uint_as_float(w & 0xffff0000u);
+  double acc = fma(d1, d1, d0 * d0);
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) acc += __shfl_xor(acc, o);
+  return acc;
+}
+
 // grid (ceil(L / 256), G).  x [G][L][128], cb [G][N][S][128] bf16, cn [G][N][S] f32, codes [G][L][N] int32,
-// residual [G][L][128] bf16 or null.  S % 64 == 0.
+// residual [G][L][128] bf16 or null.  S % 64 == 0.  stats (optional): [0] += decisions re-evaluated exactly.
 __global__ __launch_bounds__(256, 2)
 void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cb, const float* __restrict__ cn,
-                       int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual) {
-  __shared__ __attribute__((aligned(256))) unsigned char buf[2][kRvqChunk * 256];
-  __shared__ int zbuf[4][64];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+                       int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual, int32_t* __restrict__ stats) {
+  // three stages of a chunk each: chunk t is computed on while chunks t+1 and t+2 are on their way (one chunk ahead, the
+  // wait for it at the end of every chunk costs about a memory latency: measured, the MFMA-only loop ran at half speed)
+  // The fragment reads of the main loop are inline assembly with the wavefront's own waits (lds_read16 / lds_wait below): the
+  // compiler, seeing a read of an LDS array that loads in flight may write to, would wait for all of them before every read.
+  __shared__ __attribute__((aligned(1024))) unsigned char bufs[3][kRvqChunk * 256];
+  __shared__ __attribute__((aligned(256))) float nrms[3][kRvqChunk];
+  __shared__ RvqResolveLds rq;                    // exact re-evaluation at the end of a stage
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int e16 = lane & 15, kq = lane >> 4;
   const int g = blockIdx.y;
   const int v0 = blockIdx.x * kRvqVecs + wave * 64;
@@ -67,124 +135,337 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   cb += (int64_t)g * N * S * kRvqD; cn += (int64_t)g * N * S;
   if (residual) residual += (int64_t)g * L * kRvqD;
 
-  // residuals in operand layout: ra[rb][ks] = row 16 rb + l%16, k = 32 ks + 8 (l/16) .. +7
+  // residuals in operand layout: ra[rb][ks] = vector 16 rb + l%16, k = 32 ks + 8 (l/16) .. +7
   u32x4_t ra[4][4];
+  float rn2[4];                                   // squared norm of the lane's four vectors (f32, all 128 components)
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
     int v = v0 + rb * 16 + e16; v = v < L ? v : L - 1;
+    float a = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) ra[rb][ks] = *reinterpret_cast<const u32x4_t*>(x + (int64_t)v * kRvqD + ks * 32 + kq * 8);
+    for (int ks = 0; ks < 4; ++ks) {
+      ra[rb][ks] = *reinterpret_cast<const u32x4_t*>(x + (int64_t)v * kRvqD + ks * 32 + kq * 8);
+      a = rvq_sumsq(ra[rb][ks], a);
+    }
+    a += __shfl_xor(a, 16); a += __shfl_xor(a, 32);
+    rn2[rb] = a;
   }
 
   const int nch = S / kRvqChunk, total = N * nch;
-  // staging: thread t moves pieces q = t + 256 j (j = 0..3) of a chunk: entry q/16, LDS slot q%16, i.e. source piece slot ^ (entry & 15)
-  u32x4_t st[4];
-  float cnn[4], cnc[4];
-  auto fetch = [&](int t) __attribute__((always_inline)) {      // chunk t of the linear sequence (stage t / nch, chunk t % nch)
-    const bf16_t* base = cb + (int64_t)t * kRvqChunk * kRvqD;    // chunks of consecutive stages are consecutive in memory
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int q = tid + 256 * j, ent = q >> 4, piece = (q & 15) ^ (ent & 15);
-      st[j] = *reinterpret_cast<const u32x4_t*>(base + ent * kRvqD + piece * 8);
-    }
-#pragma unroll
-    for (int c = 0; c < 4; ++c) cnn[c] = cn[(int64_t)t * kRvqChunk + c * 16 + e16];
-  };
-  auto stash = [&](int b) __attribute__((always_inline)) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(buf[b] + (tid + 256 * j) * 16) = st[j];
+  // staging: chunk t of the linear sequence (stage t / nch, chunk t % nch; consecutive in memory) goes straight from
+  // global memory into LDS.  Wavefront w, load j writes pieces q = 64 (4 j + w) + l: entry q / 16, LDS slot q % 16,
+  // which holds source piece slot ^ (entry & 15); wavefront 0 also brings the chunk's 64 squared norms.
+  // (entry & 15 = (4 w + l/16) & 15 does not depend on j: one lane offset serves all four loads, 16 entries apart)
+  const unsigned lane_off = (unsigned)((4 * wave + kq) * kRvqD + 8 * (e16 ^ ((4 * wave + kq) & 15)));
+  // load j (of four) of chunk t; the loads of the next chunk are issued one per block of the current one, because a
+  // global -> LDS load stalls its wavefront longest when all four wavefronts issue at the same moment
+  auto stage_in1 = [&](int t, int j, unsigned loff, unsigned ln, unsigned char* dst, float* ndst) __attribute__((always_inline)) {
+    const bf16_t* base = cb + (int64_t)t * kRvqChunk * kRvqD;
+    load16_to_lds(base + 16 * j * kRvqD + loff, dst + 64 * (4 * j + wave) * 16);
+    // the chunk's 64 squared norms: every wavefront brings them (the same bytes to the same place) rather than one of them
+    // behind a branch - the chunk loop stays one straight line of code, which is what lets its instruction order be pinned
+    if (j == 0) __builtin_amdgcn_global_load_lds((glb_ptr_t)(cn + (int64_t)t * kRvqChunk + ln), (lds_ptr_t)ndst, 4, 0, 0);
   };
 
-  fetch(0);
-  stash(0);
 #pragma unroll
-  for (int c = 0; c < 4; ++c) cnc[c] = cnn[c];
-  __syncthreads();
+  for (int j = 0; j < 4; ++j) stage_in1(0, j, lane_off, lane, bufs[0], nrms[0]);
+  if (tid == 0) rq.n = 0;
+  if (tid < kRvqSlots) rq.count[tid] = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) stage_in1(total > 1 ? 1 : 0, j, lane_off, lane, bufs[1], nrms[1]);
+  // all but the five loads of the second chunk, i.e. the first chunk has landed; then everybody's part of it
+  __builtin_amdgcn_s_waitcnt(0x0075);             // vmcnt(5) lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
-  float best[4][4]; int bidx[4][4];
-  for (int t = 0; t < total; ++t) {
-    const int ch = t % nch, stage = t / nch;
-    if (ch == 0) {
+  float best[4], second[4], cmax2 = 0.f;
+  int bidx[4];
+  const float NEG = -__builtin_inff();
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+  for (int rb = 0; rb < 4; ++rb) { best[rb] = NEG; second[rb] = NEG; bidx[rb] = 0; }
+
+  // scores of the last block of a chunk: folded into the running best under the first MFMAs of the next chunk (at the
+  // start of a stage they are -inf, which changes nothing)
+  floatx4 tail[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { best[rb][e] = -__builtin_inff(); bidx[rb][e] = 0; }
-    }
-    if (t + 1 < total) fetch(t + 1);
-    const unsigned char* cur = buf[t & 1];
-    // the accumulators start at -|c|^2/2 of their column, so the MFMAs leave the score r.c - |c|^2/2 directly
-    floatx4 acc[4][4];
+  for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      const float h = -0.5f * cnc[c];
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[rb][c][e] = h;
-    }
-    // codebook fragments are read one k-step ahead of the MFMAs that use them
-    u32x4_t fb[2][4];
-    auto frag = [&](int set, int ks) __attribute__((always_inline)) {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) fb[set][c] = *reinterpret_cast<const u32x4_t*>(cur + (c * 16 + e16) * 256 + (((ks * 4 + kq) ^ e16) << 4));
+    for (int e = 0; e < 4; ++e) tail[rb][e] = NEG;
+
+  int t = 0, stg = 0;
+  for (int stage = 0; stage < N; ++stage) {
+   for (int ch = 0; ch < nch; ++ch, ++t) {
+    // chunk t sits in stage t % 3 (= stg) and chunk t + 2 goes to stage (t + 2) % 3, which chunk t - 1 was the last to read
+    const int stg2 = stg == 0 ? 2 : stg - 1;
+    const unsigned cur_a = (unsigned)(uintptr_t)(lds_ptr_t)&bufs[0][0] + (unsigned)stg * (kRvqChunk * 256);     // LDS byte addresses
+    const unsigned ncur_a = (unsigned)(uintptr_t)(lds_ptr_t)&nrms[0][0] + (unsigned)stg * (kRvqChunk * 4);
+    unsigned char* nxt = bufs[stg2];
+    float* nnxt = nrms[stg2];
+    const int tn = t + 2 < total ? t + 2 : total - 1;   // past the end: a harmless re-load of the last chunk (no branch in the chunk body)
+
+    // One block = 16 entries against the wavefront's 64 vectors: 16 MFMAs (4 k-steps x 4 vector blocks).  Accumulator
+    // element e of acc[rb] is the score of entry 16 c + 4 (l/16) + e against vector 16 rb + l%16.
+    // The four blocks of a chunk are software-pipelined by hand, one region per block (the scheduler may not move
+    // instructions across a region border, which also keeps it from hoisting every read of the chunk to the top and running
+    // out of registers): region c holds the fragment and norm reads of block c+1, one load of the next chunk, the 16 MFMAs
+    // of block c and the 64 running-best updates of block c-1 (region 0: of the previous chunk's last block), and inside a
+    // region the order is pinned to one MFMA, four updates, one MFMA, ...: a wavefront alone then keeps both pipelines busy.
+    floatx4 acc[2][4];
+    u32x4_t fa[2][4], nqr[2];
+    // LDS offsets of the lane's fragment pieces, derived from the lane number inside the loop (a handful of operations per
+    // chunk): kept across the loop they would be a dozen loop-invariant registers, which the register allocator spills
+    int lq = lane;
+    asm volatile("" : "+v"(lq));
+    const int le16 = lq & 15, lkq = lq >> 4;
+    const int frag0 = le16 * 256 + ((lkq ^ le16) << 4);          // k-step ks: frag0 ^ (ks << 6) (bits 6-7 hold (l%16)/4 ^ ks)
+    const unsigned loff = (unsigned)((4 * wave + lkq) * kRvqD + 8 * (le16 ^ ((4 * wave + lkq) & 15)));   // = lane_off
+    // read j (of five) of block c: four fragment pieces and the lane's four squared norms (raw: not to be used before lds_wait)
+    auto read1 = [&](int c, int j, u32x4_t (&f)[4], u32x4_t& nq) __attribute__((always_inline)) {
+      if (j == 4) asm volatile("ds_read_b128 %0, %1" : "=v"(nq) : "v"(ncur_a + (unsigned)(c * 16 + lkq * 4) * 4u));
+      else asm volatile("ds_read_b128 %0, %1" : "=v"(f[j]) : "v"(cur_a + (unsigned)(c * 4096 + (frag0 ^ (j << 6)))));
     };
-    frag(0, 0);
+    // ... and wait for them (everything this wavefront has asked of LDS): the registers go through the statement, so that no use moves above it
+    auto lds_wait = [&](u32x4_t (&f)[4], u32x4_t& nq) __attribute__((always_inline)) {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(nq));
+    };
+    // running (best, second best, index) of vector block rb against one more score; candidates arrive in increasing index,
+    // so a later equal score never replaces the index; the index kept is the one without the lane's 4 (l/16) offset (uniform)
+    auto update1 = [&](int rb, float v, int code) __attribute__((always_inline)) {
+#ifndef RVQ_PROBE_NO_UPDATE
+      const bool gt = v > best[rb];
+      second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], v);
+      bidx[rb] = gt ? code : bidx[rb];
+#endif
+      best[rb] = __builtin_amdgcn_fmed3f(best[rb], v, __builtin_inff());     // the larger of the two, as one operation (fmaxf also canonicalises its inputs)
+    };
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks < 3) frag((ks + 1) & 1, ks + 1);
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          acc[rb][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ra[rb][ks]), __builtin_bit_cast(bf16x8, fb[ks & 1][c]), acc[rb][c], 0, 0, 0);
-    }
-    // scores r.c - |c|^2/2 of rows 16 rb + 4 (l/16) + e against entries ch*64 + 16 c + l%16; candidates come in increasing index
+    for (int j = 0; j < 5; ++j) read1(0, j, fa[0], nqr[0]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      const int idx = ch * kRvqChunk + c * 16 + e16;
+      lds_wait(fa[c & 1], nqr[c & 1]);
+      floatx4 h;
+      {
+        const floatx4 q = __builtin_bit_cast(floatx4, nqr[c & 1]);
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+        for (int e = 0; e < 4; ++e) { h[e] = -0.5f * q[e]; cmax2 = fmaxf(cmax2, q[e]); }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // 16 steps, each fenced off so that the order written is the order issued: one MFMA of block c (k-step i / 4, vector
+      // block i % 4), one score of the previous block folded into the running best (four vector operations), and in the early
+      // steps one of the reads of block c + 1 or this region's load of the chunk after next
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float v = acc[rb][c][e];
-          if (v > best[rb][e]) { best[rb][e] = v; bidx[rb][e] = idx; }
-        }
-    }
-    if (ch == nch - 1) {
-      // merge the 16 lanes that hold the same rows: higher score wins, equal scores go to the lower index
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float bv = best[rb][e]; int bi = bidx[rb][e];
-#pragma unroll
-          for (int o = 1; o < 16; o <<= 1) {
-            const float ov = __shfl_xor(bv, o); const int oi = __shfl_xor(bi, o);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-          }
-          if (e16 == 0) zbuf[wave][rb * 16 + kq * 4 + e] = bi;
-        }
-      __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0): zbuf visible to the own wavefront (same-wave LDS ordering)
-      const bf16_t* stage_cb = cb + (int64_t)stage * S * kRvqD;
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        const int z = zbuf[wave][rb * 16 + e16];
-        const int v = v0 + rb * 16 + e16;
-        if (kq == 0 && v < L) codes[(int64_t)v * N + stage] = z;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const u32x4_t cz = *reinterpret_cast<const u32x4_t*>(stage_cb + (int64_t)z * kRvqD + ks * 32 + kq * 8);
-          ra[rb][ks] = rvq_sub_bf16(ra[rb][ks], cz);
-        }
+      for (int i = 0; i < 16; ++i) {
+        const int ks = i >> 2, rb = i & 3;
+#ifdef RVQ_PROBE_NO_MFMA
+        acc[c & 1][rb] = h;
+#else
+        acc[c & 1][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fa[c & 1][ks]), __builtin_bit_cast(bf16x8, ra[rb][ks]),
+                                                              ks == 0 ? h : acc[c & 1][rb], 0, 0, 0);
+#endif
+        if (c < 3 && i < 5) read1(c + 1, i, fa[(c + 1) & 1], nqr[(c + 1) & 1]);
+        if (i == 6) stage_in1(tn, c, loff, (unsigned)lq, nxt, nnxt);
+        // score e = i / 4 of vector block i % 4 of the previous block (region 0: of the previous chunk's last block)
+        if (c == 0) update1(rb, tail[rb][ks], (ch - 1) * kRvqChunk + 48 + ks);
+        else update1(rb, acc[(c - 1) & 1][rb][ks], ch * kRvqChunk + (c - 1) * 16 + ks);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
-    if (t + 1 < total) {
-      stash((t + 1) & 1);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) cnc[c] = cnn[c];
+    for (int rb = 0; rb < 4; ++rb) tail[rb] = acc[1][rb];
+    stg = stg == 2 ? 0 : stg + 1;
+    // End of a chunk: all but this chunk's own five loads have landed (the next chunk is complete once everybody is here) and
+    // the wavefront's fragment reads are done (the stage may be overwritten).  Written out instead of __syncthreads(), whose
+    // fence would wait for the loads of the chunk after next as well; nothing but LDS is shared here.
+    __builtin_amdgcn_s_waitcnt(0x0075);           // vmcnt(5) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");                // (the compiler keeps LDS accesses on their side of the barrier)
+   }
+    {
+      // ---- end of a stage: the last block's scores, then merge the four lanes that share a vector (their entries differ
+      // by 4 (l/16))
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) {
+          const float v = tail[rb][e];
+          const bool gt = v > best[rb];
+          second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], v);
+          bidx[rb] = gt ? (nch - 1) * kRvqChunk + 48 + e : bidx[rb];
+          best[rb] = fmaxf(best[rb], v);
+          tail[rb][e] = NEG;
+        }
+      const float cm = fmaxf(fmaxf(cmax2, __shfl_xor(cmax2, 16)), __shfl_xor(fmaxf(cmax2, __shfl_xor(cmax2, 16)), 32));
+      const bf16_t* stage_cb = cb + (int64_t)stage * S * kRvqD;
+      int z[4];
+      bool amb[4];
+      float margin[4], bestm[4];
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        float b = best[rb], s2 = second[rb];
+        int bi = bidx[rb] + 4 * kq;
+#pragma unroll
+        for (int o = 16; o < 64; o <<= 1) {
+          const float ob = __shfl_xor(b, o), os = __shfl_xor(s2, o);
+          const int oi = __shfl_xor(bi, o);
+          s2 = fmaxf(fminf(b, ob), fmaxf(s2, os));
+          if (ob > b || (ob == b && oi < bi)) bi = oi;
+          b = fmaxf(b, ob);
+        }
+        z[rb] = bi;
+        bestm[rb] = b;
+        // the winner is certain when its lead exceeds what rounding can have done to two scores
+        margin[rb] = kRvqGamma2 * (sqrtf(rn2[rb] * 1.0001f * cm) + 0.5f * cm);
+        amb[rb] = !(b - s2 > margin[rb]);
+#ifdef RVQ_MEASURE_WITHOUT_EXACT_PATH                       // timing probes only: never defined in the library build
+        amb[rb] = false;
+#endif
+      }
+      // ---- vectors without a certain winner: exact re-evaluation by the whole workgroup, kRvqSlots vectors per round
+      // (the four lanes of a vector agree on the flag: bit 16 rb + l%16 of the list is taken from the lanes with l/16 = 0)
+      unsigned long long todo = 0;
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) todo |= (__ballot(amb[rb]) & 0xffffull) << (16 * rb);
+      if (stats && lane == 0 && todo) atomicAdd(stats, __builtin_popcountll(todo));
+      const float* stage_cn = cn + (int64_t)stage * S;
+      // (rq.n and rq.count are zero on entry: cleared at the start of the kernel and at the end of every round that used them,
+      // with a workgroup barrier between that and the next claim; the usual stage, with nothing to resolve, costs one barrier)
+      for (;;) {
+        // claim slots, lowest vector first; a vector that gets none this round keeps its bit
+        unsigned long long rest = todo;
+        while (rest) {
+          const int bit = __builtin_ctzll(rest);
+          rest &= rest - 1;
+          int slot = 0;
+          if (lane == 0) slot = atomicAdd(&rq.n, 1);
+          slot = __shfl(slot, 0);
+          if (slot >= kRvqSlots) continue;
+          todo &= ~(1ull << bit);
+          const int rbs = bit >> 4, e = bit & 15;
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
+            if (rb == rbs && e16 == e) {
+#pragma unroll
+              for (int ks = 0; ks < 4; ++ks) rq.bits[slot][ks * 4 + kq] = ra[rb][ks];
+              if (kq == 0) { rq.margin[slot] = margin[rb]; rq.best[slot] = bestm[rb]; rq.owner[slot] = 64 * wave + bit; }
+            }
+        }
+        __syncthreads();
+        const int asked = rq.n;
+        if (asked == 0) break;                             // (the same for every wavefront)
+        const int nslot = asked < kRvqSlots ? asked : kRvqSlots;
+        {
+          // 1. + 2.: column l%16 of the B operand is the vector of slot l%16; this wavefront takes a quarter of the entries
+          const bool live = e16 < nslot;
+          const float mg = live ? rq.margin[e16] : 0.f;
+          u32x4_t bq[4];
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) bq[ks] = rq.bits[e16][ks * 4 + kq];      // (stale data in unused slots: never looked at)
+          float lmax = live ? rq.best[e16] - mg : NEG;
+          const int nblk = S / 16, per = nblk / 4;         // S % 64 == 0: a whole number of groups per wavefront
+#ifndef RVQ_PROBE_NO_PASS
+#pragma unroll 1
+          for (int blk0 = wave * per; blk0 < (wave + 1) * per; blk0 += 4) {
+            u32x4_t a[4][4];
+            floatx4 h[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int blk = blk0 + u < (wave + 1) * per ? blk0 + u : blk0;         // per may not be a multiple of four: redo a group
+              const bf16_t* ent = stage_cb + (int64_t)(blk * 16 + e16) * kRvqD + kq * 8;
+#pragma unroll
+              for (int ks = 0; ks < 4; ++ks) a[u][ks] = *reinterpret_cast<const u32x4_t*>(ent + ks * 32);
+              h[u] = *reinterpret_cast<const floatx4*>(stage_cn + blk * 16 + 4 * kq);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              if (blk0 + u >= (wave + 1) * per) break;
+              floatx4 acc;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[e] = -0.5f * h[u][e];
+#pragma unroll
+              for (int ks = 0; ks < 4; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u][ks]), __builtin_bit_cast(bf16x8, bq[ks]), acc, 0, 0, 0);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {                // element e: entry 16 (blk0 + u) + 4 (l/16) + e against the vector of slot l%16
+                const float v = acc[e];
+                lmax = fmaxf(lmax, v);
+                if (live && !(lmax - v > mg)) {
+                  const int pos = atomicAdd(&rq.count[e16], 1);
+                  if (pos < kRvqCand) { rq.cand[e16][pos] = (blk0 + u) * 16 + 4 * kq + e; rq.cscore[e16][pos] = v; }
+                }
+              }
+            }
+          }
+#endif
+          rq.top[e16][wave * 4 + kq] = lmax;
+        }
+        __syncthreads();
+        // 3.: wavefront w decides slots w, w + 4, ...
+#ifndef RVQ_PROBE_NO_DECIDE
+        for (int j = wave; j < nslot; j += 4) {
+          float top = rq.top[j][lane & 15];
+#pragma unroll
+          for (int o = 1; o < 16; o <<= 1) top = fmaxf(top, __shfl_xor(top, o));
+          const float mg = rq.margin[j];
+          const int listed = rq.count[j];
+          double dmin = __builtin_inf();
+          int imin = 0x7fffffff;
+          if (listed > kRvqCand) {                         // the list overflowed: every entry, one after the other
+#pragma unroll 1
+            for (int ent = 0; ent < S; ++ent) {
+              const double d = rvq_exact_distance(rq, j, stage_cb, ent, lane);
+              if (d < dmin) { dmin = d; imin = ent; }
+            }
+          } else {
+#pragma unroll 1
+            for (int i = 0; i < listed; ++i) {
+              if (top - rq.cscore[j][i] > mg) continue;
+              const int ent = rq.cand[j][i];
+              const double d = rvq_exact_distance(rq, j, stage_cb, ent, lane);
+              if (d < dmin || (d == dmin && ent < imin)) { dmin = d; imin = ent; }
+            }
+          }
+          if (lane == 0) rq.result[j] = imin;
+        }
+#else
+        if (tid < kRvqSlots) rq.result[tid] = 0;
+#endif
+        __syncthreads();
+        for (int j = 0; j < nslot; ++j) {                  // the owners collect their answers
+          const int o = rq.owner[j];
+          if ((o >> 6) != wave) continue;
+          const int rbs = (o >> 4) & 3, e = o & 15, zz = rq.result[j];
+          if ((unsigned)zz >= (unsigned)S) continue;       // no survivor (scores that are not numbers): the main pass's index stands
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
+            if (rb == rbs && e16 == e) z[rb] = zz;
+        }
+        __syncthreads();                                   // everybody has read this round's requests and answers
+        if (tid == 0) rq.n = 0;
+        if (tid < kRvqSlots) rq.count[tid] = 0;
+        if (asked <= kRvqSlots) break;
+        __syncthreads();                                   // cleared before the next round's claims
+      }
+      // ---- codes out, residual update, its squared norm for the next stage's margin
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        const int v = v0 + rb * 16 + e16;
+        if (kq == 0 && v < L) codes[(int64_t)v * N + stage] = z[rb];
+        float a = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          const u32x4_t cz = *reinterpret_cast<const u32x4_t*>(stage_cb + (int64_t)z[rb] * kRvqD + ks * 32 + kq * 8);
+          ra[rb][ks] = rvq_sub_bf16(ra[rb][ks], cz);
+          a = rvq_sumsq(ra[rb][ks], a);
+        }
+        a += __shfl_xor(a, 16); a += __shfl_xor(a, 32);
+        rn2[rb] = a;
+        best[rb] = NEG; second[rb] = NEG; bidx[rb] = 0;
+      }
+      cmax2 = 0.f;
     }
-    __syncthreads();
   }
+  __builtin_amdgcn_s_waitcnt(0x0F70);             // vmcnt(0): no load into LDS may be in flight when the workgroup gives its LDS back
   if (residual) {
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb) {

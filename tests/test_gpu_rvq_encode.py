@@ -90,3 +90,39 @@ def test_rvq_encode_ties_and_exact_recovery():
     np.testing.assert_array_equal(codes[0].cpu().numpy(), want)
     assert not bool((codes == 40).any())
     assert float(res.float().abs().max()) == 0.0
+
+
+def test_rvq_encode_near_ties_are_decided_exactly():
+    """Entries in near-duplicate pairs: entry 2s+1 equals entry 2s except for 2^-20 in a component where 2s holds zero.
+    The two scores differ by about 1e-6 of their size - below what float32 accumulation resolves, so which one wins
+    depends on exact arithmetic.  Every decision must still equal the float64 oracle's, and the counter of decisions
+    re-evaluated exactly must show that this path did the work."""
+    G, L, N, S, D = 1, 300, 4, 128, 128
+    x, cb = synth.make_rvq_case(G, L, N, S, D, seed=0x5EED0200, device="cuda")
+    cb = cb.clone()
+    sign = torch.where(torch.arange(S // 2, device="cuda") % 2 == 0, 1.0, -1.0).to(torch.bfloat16)
+    cb[:, :, 0::2, 0] = 0
+    cb[:, :, 1::2, :] = cb[:, :, 0::2, :]
+    cb[:, :, 1::2, 0] = (sign * 2.0 ** -20).view(1, 1, -1)
+    n_exact = torch.zeros(1, dtype=torch.int32, device="cuda")
+    codes, res = binding.rl_rvq_encode(x, cb, count_exact=n_exact)
+    torch.cuda.synchronize()
+    want, want_res = rvq.rvq_encode(_bits(x[0]), _bits(cb[0]))
+    got = codes[0].cpu().numpy()
+    assert (got % 2 == 1).any() and (got % 2 == 0).any()            # both members of pairs win somewhere
+    np.testing.assert_array_equal(got, want)
+    np.testing.assert_array_equal(_bits(res[0]), want_res)
+    n = int(n_exact.item())
+    print("decisions re-evaluated exactly:", n, "of", L * N)
+    assert n >= L * N
+
+
+def test_rvq_encode_exact_path_is_rare_on_ordinary_inputs():
+    G, L, N, S = 2, 1024, 16, 1024
+    x, cb = synth.make_rvq_case(G, L, N, S, device="cuda")
+    n_exact = torch.zeros(1, dtype=torch.int32, device="cuda")
+    binding.rl_rvq_encode(x, cb, count_exact=n_exact)
+    torch.cuda.synchronize()
+    n = int(n_exact.item())
+    print("decisions re-evaluated exactly:", n, "of", G * L * N)
+    assert n <= 0.01 * G * L * N
