@@ -114,11 +114,11 @@ __device__ __attribute__((always_inline)) inline double rvq_exact_distance(const
   return acc;
 }
 
-// grid (ceil(L / 256), G).  x [G][L][128], cb [G][N][S][128] bf16, cn [G][N][S] f32, codes [G][L][N] int32,
+// grid 8 ceil(G / 8) ceil(L / 256) workgroups (see the kernel for who takes what).  x [G][L][128], cb [G][N][S][128] bf16, cn [G][N][S] f32, codes [G][L][N] int32,
 // residual [G][L][128] bf16 or null.  S % 64 == 0.  stats (optional): [0] += decisions re-evaluated exactly.
 __global__ __launch_bounds__(256, 2)
 void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cb, const float* __restrict__ cn,
-                       int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual, int32_t* __restrict__ stats) {
+                       int G, int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual, int32_t* __restrict__ stats) {
   // three stages of a chunk each: chunk t is computed on while chunks t+1 and t+2 are on their way (one chunk ahead, the
   // wait for it at the end of every chunk costs about a memory latency: measured, the MFMA-only loop ran at half speed)
   // The fragment reads of the main loop are inline assembly with the wavefront's own waits (lds_read16 / lds_wait below): the
@@ -129,8 +129,13 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int e16 = lane & 15, kq = lane >> 4;
-  const int g = blockIdx.y;
-  const int v0 = blockIdx.x * kRvqVecs + wave * 64;
+  // Workgroups are handed to the eight XCDs in turn (w % 8), each with an L2 of its own.  The workgroups of one group read the
+  // same codebooks at the same time, so they are given numbers w that agree modulo 8: on its XCD, workgroup q = w / 8 takes
+  // block q % gx of group 8 (q / gx) + w % 8, and the codebooks come out of memory once instead of once per block.
+  const int w = blockIdx.x, gx = (L + kRvqVecs - 1) / kRvqVecs;
+  const int g = 8 * ((w >> 3) / gx) + (w & 7);
+  if (g >= G) return;                             // (the whole workgroup: the grid covers ceil(G / 8) * 8 groups)
+  const int v0 = ((w >> 3) % gx) * kRvqVecs + wave * 64;
   x += (int64_t)g * L * kRvqD; codes += (int64_t)g * L * N;
   cb += (int64_t)g * N * S * kRvqD; cn += (int64_t)g * N * S;
   if (residual) residual += (int64_t)g * L * kRvqD;
@@ -152,6 +157,10 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   }
 
   const int nch = S / kRvqChunk, total = N * nch;
+#ifdef RVQ_PROBE_STAGGER                                 // timing probe: some workgroups start late by RVQ_PROBE_STAGGER_SLEEPS x ~4 us
+  if (((w >> 3) >> RVQ_PROBE_STAGGER) & 1)
+    for (int i = 0; i < RVQ_PROBE_STAGGER_SLEEPS; ++i) __builtin_amdgcn_s_sleep(127);
+#endif
   // staging: chunk t of the linear sequence (stage t / nch, chunk t % nch; consecutive in memory) goes straight from
   // global memory into LDS.  Wavefront w, load j writes pieces q = 64 (4 j + w) + l: entry q / 16, LDS slot q % 16,
   // which holds source piece slot ^ (entry & 15); wavefront 0 also brings the chunk's 64 squared norms.
@@ -178,11 +187,19 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
-  float best[4], second[4], cmax2 = 0.f;
-  int bidx[4];
+  // Running arg-max per vector block, kept per block of four scores (the lane's entries 16 b + 4 (l/16) + 0..3 of block b): the
+  // largest block maximum so far, the second largest, the block that holds the largest, and that block's four scores.  Which
+  // of the four won, and how close the others of that block came, is looked up once at the end of the stage: ten vector
+  // operations per four scores instead of sixteen.
+  float best[4], second[4], sv[4][4], cmax2 = 0.f;
+  int bblk[4];
   const float NEG = -__builtin_inff();
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb) { best[rb] = NEG; second[rb] = NEG; bidx[rb] = 0; }
+  for (int rb = 0; rb < 4; ++rb) {
+    best[rb] = NEG; second[rb] = NEG; bblk[rb] = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sv[rb][e] = NEG;
+  }
 
   // scores of the last block of a chunk: folded into the running best under the first MFMAs of the next chunk (at the
   // start of a stage they are -inf, which changes nothing)
@@ -220,23 +237,43 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
     const int frag0 = le16 * 256 + ((lkq ^ le16) << 4);          // k-step ks: frag0 ^ (ks << 6) (bits 6-7 hold (l%16)/4 ^ ks)
     const unsigned loff = (unsigned)((4 * wave + lkq) * kRvqD + 8 * (le16 ^ ((4 * wave + lkq) & 15)));   // = lane_off
     // read j (of five) of block c: four fragment pieces and the lane's four squared norms (raw: not to be used before lds_wait)
+    unsigned fbase[4];                                           // this chunk's addresses of the lane's four pieces of block 0, and of its norms
+#pragma unroll
+    for (int j = 0; j < 4; ++j) fbase[j] = cur_a + (unsigned)(frag0 ^ (j << 6));
+    const unsigned nbase = ncur_a + (unsigned)lkq * 16u;
     auto read1 = [&](int c, int j, u32x4_t (&f)[4], u32x4_t& nq) __attribute__((always_inline)) {
-      if (j == 4) asm volatile("ds_read_b128 %0, %1" : "=v"(nq) : "v"(ncur_a + (unsigned)(c * 16 + lkq * 4) * 4u));
-      else asm volatile("ds_read_b128 %0, %1" : "=v"(f[j]) : "v"(cur_a + (unsigned)(c * 4096 + (frag0 ^ (j << 6)))));
+      if (j == 4) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(nq) : "v"(nbase), "n"(c * 64));
+      else asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f[j]) : "v"(fbase[j]), "n"(c * 4096));
     };
     // ... and wait for them (everything this wavefront has asked of LDS): the registers go through the statement, so that no use moves above it
     auto lds_wait = [&](u32x4_t (&f)[4], u32x4_t& nq) __attribute__((always_inline)) {
       asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(nq));
     };
-    // running (best, second best, index) of vector block rb against one more score; candidates arrive in increasing index,
-    // so a later equal score never replaces the index; the index kept is the one without the lane's 4 (l/16) offset (uniform)
-    auto update1 = [&](int rb, float v, int code) __attribute__((always_inline)) {
+    // the four scores v of one block folded into the running state of vector block rb, in four parts u (one per MFMA step).
+    // Blocks arrive in increasing order, so a later equal maximum never replaces the block kept.
+    float m4 = 0.f;
+    bool gt = false;
+    auto fold = [&](int rb, int u, const floatx4& v, int blk) __attribute__((always_inline)) {
 #ifndef RVQ_PROBE_NO_UPDATE
-      const bool gt = v > best[rb];
-      second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], v);
-      bidx[rb] = gt ? code : bidx[rb];
+      if (u == 0) {
+        float m3;
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m3) : "v"(v[0]), "v"(v[1]), "v"(v[2]));
+        asm("v_max_f32 %0, %1, %2" : "=v"(m4) : "v"(m3), "v"(v[3]));     // (written out: fmaxf would canonicalise both inputs first)
+        gt = m4 > best[rb];
+      } else if (u == 1) {
+        bblk[rb] = gt ? blk : bblk[rb];
+        sv[rb][0] = gt ? v[0] : sv[rb][0];
+        sv[rb][1] = gt ? v[1] : sv[rb][1];
+      } else if (u == 2) {
+        sv[rb][2] = gt ? v[2] : sv[rb][2];
+        sv[rb][3] = gt ? v[3] : sv[rb][3];
+      } else {
+        second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], m4);
+        asm("v_max_f32 %0, %0, %1" : "+v"(best[rb]) : "v"(m4));
+      }
+#else
+      if (u == 0) asm("v_max_f32 %0, %0, %1" : "+v"(best[rb]) : "v"(v[0]));
 #endif
-      best[rb] = __builtin_amdgcn_fmed3f(best[rb], v, __builtin_inff());     // the larger of the two, as one operation (fmaxf also canonicalises its inputs)
     };
 #pragma unroll
     for (int j = 0; j < 5; ++j) read1(0, j, fa[0], nqr[0]);
@@ -248,12 +285,14 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
       {
         const floatx4 q = __builtin_bit_cast(floatx4, nqr[c & 1]);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { h[e] = -0.5f * q[e]; cmax2 = fmaxf(cmax2, q[e]); }
+        for (int e = 0; e < 4; ++e) h[e] = -0.5f * q[e];
+        asm("v_max3_f32 %0, %0, %1, %2" : "+v"(cmax2) : "v"(q[0]), "v"(q[1]));
+        asm("v_max3_f32 %0, %0, %1, %2" : "+v"(cmax2) : "v"(q[2]), "v"(q[3]));
       }
       __builtin_amdgcn_sched_barrier(0);
       // 16 steps, each fenced off so that the order written is the order issued: one MFMA of block c (k-step i / 4, vector
-      // block i % 4), one score of the previous block folded into the running best (four vector operations), and in the early
-      // steps one of the reads of block c + 1 or this region's load of the chunk after next
+      // block i % 4), a part of folding the previous block's scores into the running state (two or three vector operations),
+      // and in the early steps one of the reads of block c + 1 or this region's load of the chunk after next
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int ks = i >> 2, rb = i & 3;
@@ -263,11 +302,15 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         acc[c & 1][rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fa[c & 1][ks]), __builtin_bit_cast(bf16x8, ra[rb][ks]),
                                                               ks == 0 ? h : acc[c & 1][rb], 0, 0, 0);
 #endif
+#ifndef RVQ_PROBE_NO_LDSREAD
         if (c < 3 && i < 5) read1(c + 1, i, fa[(c + 1) & 1], nqr[(c + 1) & 1]);
+#endif
+#ifndef RVQ_PROBE_NO_DMA
         if (i == 6) stage_in1(tn, c, loff, (unsigned)lq, nxt, nnxt);
+#endif
         // score e = i / 4 of vector block i % 4 of the previous block (region 0: of the previous chunk's last block)
-        if (c == 0) update1(rb, tail[rb][ks], (ch - 1) * kRvqChunk + 48 + ks);
-        else update1(rb, acc[(c - 1) & 1][rb][ks], ch * kRvqChunk + (c - 1) * 16 + ks);
+        // part i % 4 of folding in the previous block's scores for vector block i / 4 (region 0: the previous chunk's last block)
+        fold(i >> 2, i & 3, c == 0 ? tail[i >> 2] : acc[(c - 1) & 1][i >> 2], ch * 4 + c - 1);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -278,23 +321,40 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
     // the wavefront's fragment reads are done (the stage may be overwritten).  Written out instead of __syncthreads(), whose
     // fence would wait for the loads of the chunk after next as well; nothing but LDS is shared here.
     __builtin_amdgcn_s_waitcnt(0x0075);           // vmcnt(5) lgkmcnt(0)
+#ifndef RVQ_PROBE_NO_SYNC
     __builtin_amdgcn_s_barrier();
+#endif
     asm volatile("" ::: "memory");                // (the compiler keeps LDS accesses on their side of the barrier)
    }
     {
       // ---- end of a stage: the last block's scores, then merge the four lanes that share a vector (their entries differ
       // by 4 (l/16))
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
+      for (int rb = 0; rb < 4; ++rb) {
+        const floatx4 v = tail[rb];
+        float m3;
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m3) : "v"(v[0]), "v"(v[1]), "v"(v[2]));
+        const float m4 = fmaxf(m3, v[3]);
+        const bool gt = m4 > best[rb];
+        bblk[rb] = gt ? nch * 4 - 1 : bblk[rb];
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) {
-          const float v = tail[rb][e];
-          const bool gt = v > best[rb];
-          second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], v);
-          bidx[rb] = gt ? (nch - 1) * kRvqChunk + 48 + e : bidx[rb];
-          best[rb] = fmaxf(best[rb], v);
-          tail[rb][e] = NEG;
-        }
+        for (int e = 0; e < 4; ++e) { sv[rb][e] = gt ? v[e] : sv[rb][e]; tail[rb][e] = NEG; }
+        second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], m4);
+        best[rb] = fmaxf(best[rb], m4);
+      }
+      // which of the kept block's four scores is the maximum (the first, if several), and the largest of the other three:
+      // that one competes for second place with the other blocks' maxima
+      int bidx[4];
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        const float b = best[rb];
+        const int e = sv[rb][0] == b ? 0 : sv[rb][1] == b ? 1 : sv[rb][2] == b ? 2 : 3;
+        float s_in = NEG;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s_in = q == e ? s_in : fmaxf(s_in, sv[rb][q]);
+        second[rb] = fmaxf(second[rb], s_in);
+        bidx[rb] = 16 * bblk[rb] + e;
+      }
       const float cm = fmaxf(fmaxf(cmax2, __shfl_xor(cmax2, 16)), __shfl_xor(fmaxf(cmax2, __shfl_xor(cmax2, 16)), 32));
       const bf16_t* stage_cb = cb + (int64_t)stage * S * kRvqD;
       int z[4];
@@ -460,7 +520,9 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         }
         a += __shfl_xor(a, 16); a += __shfl_xor(a, 32);
         rn2[rb] = a;
-        best[rb] = NEG; second[rb] = NEG; bidx[rb] = 0;
+        best[rb] = NEG; second[rb] = NEG; bblk[rb] = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sv[rb][e] = NEG;
       }
       cmax2 = 0.f;
     }
