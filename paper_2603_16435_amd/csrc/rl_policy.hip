@@ -1366,10 +1366,16 @@ rl_status rl_rvq_encode_counted(const void* vectors, const void* codebooks, cons
   if (st != RL_OK) return st;
   if ((reinterpret_cast<uintptr_t>(vectors) | reinterpret_cast<uintptr_t>(codebooks) | reinterpret_cast<uintptr_t>(residual)) & 15) return RL_ERR_SHAPE;
   (void)hipGetLastError();
-  const int64_t n_wg = (L + kRvqVecs - 1) / kRvqVecs * (8 * (((int64_t)G + 7) / 8));
+  const int kw = L > 256 ? 8 : 4;                                   // wavefronts per workgroup, 64 vectors each
+  const int64_t n_wg = (L + 64 * kw - 1) / (64 * kw) * (8 * (((int64_t)G + 7) / 8));
   if (n_wg > 0x7fffffff) return RL_ERR_RANGE;
-  rvq_encode_kernel<<<(unsigned)n_wg, 256, 0, static_cast<hipStream_t>(stream)>>>(static_cast<const bf16_t*>(vectors), static_cast<const bf16_t*>(codebooks), norms,
-                                                                       G, (int)L, N, S, codes, static_cast<bf16_t*>(residual), n_exact);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (kw == 8)
+    rvq_encode_kernel<8><<<(unsigned)n_wg, 512, 0, s>>>(static_cast<const bf16_t*>(vectors), static_cast<const bf16_t*>(codebooks), norms,
+                                                        G, (int)L, N, S, codes, static_cast<bf16_t*>(residual), n_exact);
+  else
+    rvq_encode_kernel<4><<<(unsigned)n_wg, 256, 0, s>>>(static_cast<const bf16_t*>(vectors), static_cast<const bf16_t*>(codebooks), norms,
+                                                        G, (int)L, N, S, codes, static_cast<bf16_t*>(residual), n_exact);
   return hipGetLastError() == hipSuccess ? RL_OK : RL_ERR_HIP;
 }
 

@@ -32,7 +32,8 @@ namespace rlk {
 
 constexpr int kRvqD = 128;          // head dimension the kernel is written for
 constexpr int kRvqChunk = 64;       // codebook entries per LDS chunk
-constexpr int kRvqVecs = 256;       // vectors per workgroup
+// (a workgroup of kW wavefronts takes 64 kW vectors: kW = 8, one workgroup per CU, when there are more than 256 vectors
+// in a group - the chunk in LDS then serves twice the vectors per load - else kW = 4, two workgroups per CU)
 constexpr float kRvqGamma2 = 3.0517578125e-05f;   // 2 g = 2^-15: twice the bound on the relative error of an f32 score
 
 // squared norms of the entries, f32 (products of bf16 are exact in f32; summed in index order)
@@ -96,16 +97,16 @@ struct RvqResolveLds {
   int count[kRvqSlots];                   // entries listed (may run past kRvqCand: then the list is not used)
   int cand[kRvqSlots][kRvqCand];
   float cscore[kRvqSlots][kRvqCand];
-  float top[kRvqSlots][16];               // running maxima at the end of the pass, per wavefront and lane group
+  float top[kRvqSlots][32];               // running maxima at the end of the pass, per wavefront and lane group
   int result[kRvqSlots];
   int n;                                  // vectors that asked for a slot this round (may exceed kRvqSlots: the rest go next round)
 };
 
 // Squared distance of the vector in slot j to one entry, straight from the definition in float64: lane l takes components
 // 2 l and 2 l + 1, the 64 partial sums are added in a fixed tree (the same for every entry, so equal entries give equal sums).
-__device__ __attribute__((always_inline)) inline double rvq_exact_distance(const RvqResolveLds& q, int j, const bf16_t* stage_cb, int ent, int lane) {
+__device__ __attribute__((always_inline)) inline double rvq_exact_distance(const u32x4_t* bits, const bf16_t* stage_cb, int ent, int lane) {
   const unsigned w = *reinterpret_cast<const unsigned*>(stage_cb + (int64_t)ent * kRvqD + 2 * lane);
-  const unsigned r = reinterpret_cast<const unsigned*>(&q.bits[j][0])[lane];
+  const unsigned r = reinterpret_cast<const unsigned*>(bits)[lane];
   const double d0 = (double)__uint_as_float(r << 16) - (double)__uint_as_float(w << 16);
   const double d1 = (double)__uint_as_float(r & 0xffff0000u) - (double)__uint_as_float(w & 0xffff0000u);
   double acc = fma(d1, d1, d0 * d0);
@@ -116,7 +117,8 @@ __device__ __attribute__((always_inline)) inline double rvq_exact_distance(const
 
 // grid 8 ceil(G / 8) ceil(L / 256) workgroups (see the kernel for who takes what).  x [G][L][128], cb [G][N][S][128] bf16, cn [G][N][S] f32, codes [G][L][N] int32,
 // residual [G][L][128] bf16 or null.  S % 64 == 0.  stats (optional): [0] += decisions re-evaluated exactly.
-__global__ __launch_bounds__(256, 2)
+template <int kW>
+__global__ __launch_bounds__(64 * kW, 8 / kW)
 void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cb, const float* __restrict__ cn,
                        int G, int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual, int32_t* __restrict__ stats) {
   // three stages of a chunk each: chunk t is computed on while chunks t+1 and t+2 are on their way (one chunk ahead, the
@@ -126,12 +128,14 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   __shared__ __attribute__((aligned(1024))) unsigned char bufs[3][kRvqChunk * 256];
   __shared__ __attribute__((aligned(256))) float nrms[3][kRvqChunk];
   __shared__ RvqResolveLds rq;                    // exact re-evaluation at the end of a stage
+  __shared__ u32x4_t wvec[kW][kRvqD / 8];          // ... and one vector per wavefront for what it settles by itself
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int e16 = lane & 15, kq = lane >> 4;
   // Workgroups are handed to the eight XCDs in turn (w % 8), each with an L2 of its own.  The workgroups of one group read the
   // same codebooks at the same time, so they are given numbers w that agree modulo 8: on its XCD, workgroup q = w / 8 takes
   // block q % gx of group 8 (q / gx) + w % 8, and the codebooks come out of memory once instead of once per block.
+  constexpr int kRvqVecs = 64 * kW;
   const int w = blockIdx.x, gx = (L + kRvqVecs - 1) / kRvqVecs;
   const int g = 8 * ((w >> 3) / gx) + (w & 7);
   if (g >= G) return;                             // (the whole workgroup: the grid covers ceil(G / 8) * 8 groups)
@@ -170,20 +174,20 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   // global -> LDS load stalls its wavefront longest when all four wavefronts issue at the same moment
   auto stage_in1 = [&](int t, int j, unsigned loff, unsigned ln, unsigned char* dst, float* ndst) __attribute__((always_inline)) {
     const bf16_t* base = cb + (int64_t)t * kRvqChunk * kRvqD;
-    load16_to_lds(base + 16 * j * kRvqD + loff, dst + 64 * (4 * j + wave) * 16);
+    load16_to_lds(base + 4 * kW * j * kRvqD + loff, dst + 64 * (kW * j + wave) * 16);
     // the chunk's 64 squared norms: every wavefront brings them (the same bytes to the same place) rather than one of them
     // behind a branch - the chunk loop stays one straight line of code, which is what lets its instruction order be pinned
     if (j == 0) __builtin_amdgcn_global_load_lds((glb_ptr_t)(cn + (int64_t)t * kRvqChunk + ln), (lds_ptr_t)ndst, 4, 0, 0);
   };
 
 #pragma unroll
-  for (int j = 0; j < 4; ++j) stage_in1(0, j, lane_off, lane, bufs[0], nrms[0]);
+  for (int j = 0; j < 16 / kW; ++j) stage_in1(0, j, lane_off, lane, bufs[0], nrms[0]);
   if (tid == 0) rq.n = 0;
   if (tid < kRvqSlots) rq.count[tid] = 0;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) stage_in1(total > 1 ? 1 : 0, j, lane_off, lane, bufs[1], nrms[1]);
+  for (int j = 0; j < 16 / kW; ++j) stage_in1(total > 1 ? 1 : 0, j, lane_off, lane, bufs[1], nrms[1]);
   // all but the five loads of the second chunk, i.e. the first chunk has landed; then everybody's part of it
-  __builtin_amdgcn_s_waitcnt(0x0075);             // vmcnt(5) lgkmcnt(0)
+  __builtin_amdgcn_s_waitcnt(kW == 4 ? 0x0075 : 0x0073);   // vmcnt(5 or 3) lgkmcnt(0)
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 
@@ -306,7 +310,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         if (c < 3 && i < 5) read1(c + 1, i, fa[(c + 1) & 1], nqr[(c + 1) & 1]);
 #endif
 #ifndef RVQ_PROBE_NO_DMA
-        if (i == 6) stage_in1(tn, c, loff, (unsigned)lq, nxt, nnxt);
+        if (i == 6 && (kW == 4 || (c & 1) == 0)) stage_in1(tn, kW == 4 ? c : c >> 1, loff, (unsigned)lq, nxt, nnxt);
 #endif
         // score e = i / 4 of vector block i % 4 of the previous block (region 0: of the previous chunk's last block)
         // part i % 4 of folding in the previous block's scores for vector block i / 4 (region 0: the previous chunk's last block)
@@ -320,7 +324,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
     // End of a chunk: all but this chunk's own five loads have landed (the next chunk is complete once everybody is here) and
     // the wavefront's fragment reads are done (the stage may be overwritten).  Written out instead of __syncthreads(), whose
     // fence would wait for the loads of the chunk after next as well; nothing but LDS is shared here.
-    __builtin_amdgcn_s_waitcnt(0x0075);           // vmcnt(5) lgkmcnt(0)
+    __builtin_amdgcn_s_waitcnt(kW == 4 ? 0x0075 : 0x0073);   // vmcnt(5 or 3) lgkmcnt(0)
 #ifndef RVQ_PROBE_NO_SYNC
     __builtin_amdgcn_s_barrier();
 #endif
@@ -342,51 +346,94 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], m4);
         best[rb] = fmaxf(best[rb], m4);
       }
-      // which of the kept block's four scores is the maximum (the first, if several), and the largest of the other three:
-      // that one competes for second place with the other blocks' maxima
+      // which of the kept block's four scores is the maximum (the first, if several)
       int bidx[4];
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
         const float b = best[rb];
         const int e = sv[rb][0] == b ? 0 : sv[rb][1] == b ? 1 : sv[rb][2] == b ? 2 : 3;
-        float s_in = NEG;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) s_in = q == e ? s_in : fmaxf(s_in, sv[rb][q]);
-        second[rb] = fmaxf(second[rb], s_in);
         bidx[rb] = 16 * bblk[rb] + e;
       }
       const float cm = fmaxf(fmaxf(cmax2, __shfl_xor(cmax2, 16)), __shfl_xor(fmaxf(cmax2, __shfl_xor(cmax2, 16)), 32));
       const bf16_t* stage_cb = cb + (int64_t)stage * S * kRvqD;
-      int z[4];
-      bool amb[4];
+      // The winner is certain when its lead over every other score exceeds what rounding can have done to two scores.  The
+      // scores that come within that margin are of two kinds.  Those of the lane's kept block have known entries (near[rb]: one
+      // bit per score of the block): if these are all there is, the wavefront settles the vector among them by itself.  A lane
+      // whose second-best block maximum comes that close stands for an entry nobody kept: then the whole workgroup looks again.
+      int z[4], near[4];
+      bool amb_known[4], amb_any[4];
       float margin[4], bestm[4];
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
-        float b = best[rb], s2 = second[rb];
+        float b = best[rb];
         int bi = bidx[rb] + 4 * kq;
 #pragma unroll
         for (int o = 16; o < 64; o <<= 1) {
-          const float ob = __shfl_xor(b, o), os = __shfl_xor(s2, o);
+          const float ob = __shfl_xor(b, o);
           const int oi = __shfl_xor(bi, o);
-          s2 = fmaxf(fminf(b, ob), fmaxf(s2, os));
           if (ob > b || (ob == b && oi < bi)) bi = oi;
           b = fmaxf(b, ob);
         }
         z[rb] = bi;
         bestm[rb] = b;
-        // the winner is certain when its lead exceeds what rounding can have done to two scores
         margin[rb] = kRvqGamma2 * (sqrtf(rn2[rb] * 1.0001f * cm) + 0.5f * cm);
-        amb[rb] = !(b - s2 > margin[rb]);
+        int nr = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) nr |= (!(b - sv[rb][q] > margin[rb]) ? 1 : 0) << q;
+        near[rb] = nr;
+        int cnt = __builtin_popcount(nr), unk = !(b - second[rb] > margin[rb]) ? 1 : 0;
+        cnt += __shfl_xor(cnt, 16); cnt += __shfl_xor(cnt, 32);
+        unk |= __shfl_xor(unk, 16); unk |= __shfl_xor(unk, 32);
+        amb_any[rb] = unk != 0;
+        amb_known[rb] = unk == 0 && cnt != 1;
 #ifdef RVQ_MEASURE_WITHOUT_EXACT_PATH                       // timing probes only: never defined in the library build
-        amb[rb] = false;
+        amb_any[rb] = false; amb_known[rb] = false;
 #endif
       }
-      // ---- vectors without a certain winner: exact re-evaluation by the whole workgroup, kRvqSlots vectors per round
-      // (the four lanes of a vector agree on the flag: bit 16 rb + l%16 of the list is taken from the lanes with l/16 = 0)
-      unsigned long long todo = 0;
+      unsigned long long todo = 0, mine = 0;
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) todo |= (__ballot(amb[rb]) & 0xffffull) << (16 * rb);
-      if (stats && lane == 0 && todo) atomicAdd(stats, __builtin_popcountll(todo));
+      for (int rb = 0; rb < 4; ++rb) {                     // (the four lanes of a vector agree: bit 16 rb + l%16 comes from the lanes with l/16 = 0)
+        todo |= (__ballot(amb_any[rb]) & 0xffffull) << (16 * rb);
+        mine |= (__ballot(amb_known[rb]) & 0xffffull) << (16 * rb);
+      }
+      if (stats && lane == 0 && (todo | mine)) atomicAdd(stats, __builtin_popcountll(todo) + __builtin_popcountll(mine));
+      // ---- vectors settled by their wavefront: the exact distance to each of the known near entries, the smallest wins
+      while (mine) {
+        const int bit = __builtin_ctzll(mine);
+        mine &= mine - 1;
+        const int rbs = bit >> 4, ev = bit & 15;
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb)
+          if (rb == rbs && e16 == ev) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) wvec[wave][ks * 4 + kq] = ra[rb][ks];
+          }
+        double dmin = __builtin_inf();
+        int imin = 0x7fffffff;
+        for (int kq2 = 0; kq2 < 4; ++kq2) {
+          int m = 0, blk = 0;
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb) {
+            const int mm = __shfl(near[rb], ev + 16 * kq2), bb = __shfl(bblk[rb], ev + 16 * kq2);
+            if (rb == rbs) { m = mm; blk = bb; }
+          }
+          m = __builtin_amdgcn_readfirstlane(m); blk = __builtin_amdgcn_readfirstlane(blk);
+          while (m) {
+            const int q = __builtin_ctz(m);
+            m &= m - 1;
+            const int ent = 16 * blk + 4 * kq2 + q;
+            if ((unsigned)ent >= (unsigned)S) continue;      // (cannot happen: block numbers come from the chunk loop)
+            const double d = rvq_exact_distance(&wvec[wave][0], stage_cb, ent, lane);
+            if (d < dmin || (d == dmin && ent < imin)) { dmin = d; imin = ent; }
+          }
+        }
+        if ((unsigned)imin < (unsigned)S) {
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb)
+            if (rb == rbs && e16 == ev) z[rb] = imin;
+        }
+      }
+      // ---- the others: exact re-evaluation by the whole workgroup, kRvqSlots vectors per round
       const float* stage_cn = cn + (int64_t)stage * S;
       // (rq.n and rq.count are zero on entry: cleared at the start of the kernel and at the end of every round that used them,
       // with a workgroup barrier between that and the next claim; the usual stage, with nothing to resolve, costs one barrier)
@@ -422,15 +469,16 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
 #pragma unroll
           for (int ks = 0; ks < 4; ++ks) bq[ks] = rq.bits[e16][ks * 4 + kq];      // (stale data in unused slots: never looked at)
           float lmax = live ? rq.best[e16] - mg : NEG;
-          const int nblk = S / 16, per = nblk / 4;         // S % 64 == 0: a whole number of groups per wavefront
+          const int nblk = S / 16, per = (nblk + kW - 1) / kW;
+          const int blk_end = (wave + 1) * per < nblk ? (wave + 1) * per : nblk;
 #ifndef RVQ_PROBE_NO_PASS
 #pragma unroll 1
-          for (int blk0 = wave * per; blk0 < (wave + 1) * per; blk0 += 4) {
+          for (int blk0 = wave * per; blk0 < blk_end; blk0 += 4) {
             u32x4_t a[4][4];
             floatx4 h[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-              const int blk = blk0 + u < (wave + 1) * per ? blk0 + u : blk0;         // per may not be a multiple of four: redo a group
+              const int blk = blk0 + u < blk_end ? blk0 + u : blk0;         // per may not be a multiple of four: redo a group
               const bf16_t* ent = stage_cb + (int64_t)(blk * 16 + e16) * kRvqD + kq * 8;
 #pragma unroll
               for (int ks = 0; ks < 4; ++ks) a[u][ks] = *reinterpret_cast<const u32x4_t*>(ent + ks * 32);
@@ -438,7 +486,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-              if (blk0 + u >= (wave + 1) * per) break;
+              if (blk0 + u >= blk_end) break;
               floatx4 acc;
 #pragma unroll
               for (int e = 0; e < 4; ++e) acc[e] = -0.5f * h[u][e];
@@ -457,15 +505,15 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
             }
           }
 #endif
-          rq.top[e16][wave * 4 + kq] = lmax;
+          rq.top[e16][wave * 4 + kq] = lmax;            // (a wavefront without entries writes its floor: the main pass's best minus the margin, or -inf)
         }
         __syncthreads();
         // 3.: wavefront w decides slots w, w + 4, ...
 #ifndef RVQ_PROBE_NO_DECIDE
-        for (int j = wave; j < nslot; j += 4) {
-          float top = rq.top[j][lane & 15];
+        for (int j = wave; j < nslot; j += kW) {
+          float top = rq.top[j][lane & (4 * kW - 1)];
 #pragma unroll
-          for (int o = 1; o < 16; o <<= 1) top = fmaxf(top, __shfl_xor(top, o));
+          for (int o = 1; o < 4 * kW; o <<= 1) top = fmaxf(top, __shfl_xor(top, o));
           const float mg = rq.margin[j];
           const int listed = rq.count[j];
           double dmin = __builtin_inf();
@@ -473,7 +521,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
           if (listed > kRvqCand) {                         // the list overflowed: every entry, one after the other
 #pragma unroll 1
             for (int ent = 0; ent < S; ++ent) {
-              const double d = rvq_exact_distance(rq, j, stage_cb, ent, lane);
+              const double d = rvq_exact_distance(&rq.bits[j][0], stage_cb, ent, lane);
               if (d < dmin) { dmin = d; imin = ent; }
             }
           } else {
@@ -481,7 +529,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
             for (int i = 0; i < listed; ++i) {
               if (top - rq.cscore[j][i] > mg) continue;
               const int ent = rq.cand[j][i];
-              const double d = rvq_exact_distance(rq, j, stage_cb, ent, lane);
+              const double d = rvq_exact_distance(&rq.bits[j][0], stage_cb, ent, lane);
               if (d < dmin || (d == dmin && ent < imin)) { dmin = d; imin = ent; }
             }
           }
