@@ -231,15 +231,18 @@ struct EpiFwdStash {
     for (int bj = 0; bj < NB; ++bj) {
 #pragma unroll
       for (int off = 16; off < 64; off <<= 1) { sm[bj] += __shfl_xor(sm[bj], off); su[bj] += __shfl_xor(su[bj], off); }
-      if (c.lane < 16) red[c.wm * BN + c.wn * (BN / WAVES_N) + perm_col(bj, cc)] = make_float2(sm[bj], su[bj] * zs);
+      // (slot 16 bj + cc of the wavefront's 128 columns, not column 8 cc + bj: the sixteen lanes then write neighbouring slots)
+      if (c.lane < 16) red[c.wm * BN + c.wn * (BN / WAVES_N) + bj * 16 + cc] = make_float2(sm[bj], su[bj] * zs);
     }
     __syncthreads();
     if (c.tid < BN) {
       const int n = c.tile_n * BN + c.tid;
       if (n < c.Nv) {
-        float2 r = red[c.tid];
+        static_assert(BN / WAVES_N == 128, "slot numbering of the staging array");
+        const int slot = (c.tid & ~127) + (c.tid & 7) * 16 + ((c.tid & 127) >> 3);
+        float2 r = red[slot];
 #pragma unroll
-        for (int w = 1; w < WAVES_M; ++w) { const float2 o2 = red[w * BN + c.tid]; r.x += o2.x; r.y += o2.y; }
+        for (int w = 1; w < WAVES_M; ++w) { const float2 o2 = red[w * BN + slot]; r.x += o2.x; r.y += o2.y; }
         part[(int64_t)c.tile_m * ldp + n] = r;
       }
     }

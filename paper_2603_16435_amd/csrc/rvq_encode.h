@@ -54,12 +54,15 @@ __global__ void rvq_norms_kernel(const bf16_t* cb, int64_t entries, float* cn) {
   cn[s] = acc;
 }
 
-__device__ inline u32x4_t rvq_sub_bf16(const u32x4_t& r, const u32x4_t& c) {   // bf16(r - c) on eight packed values
+// bf16(r - c) on eight packed values; ss += the squares of the eight differences before they are rounded (a bound on the new
+// vector's squared norm to one part in 2^7, which is all the margin needs of it)
+__device__ inline u32x4_t rvq_sub_bf16(const u32x4_t& r, const u32x4_t& c, float& ss) {
   u32x4_t o;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const float lo = __uint_as_float(r[j] << 16) - __uint_as_float(c[j] << 16);
     const float hi = __uint_as_float(r[j] & 0xffff0000u) - __uint_as_float(c[j] & 0xffff0000u);
+    ss = fmaf(lo, lo, ss); ss = fmaf(hi, hi, ss);
     bf16x2 p; p[0] = (bf16_t)lo; p[1] = (bf16_t)hi;
     o[j] = __builtin_bit_cast(unsigned, p);
   }
@@ -73,6 +76,25 @@ __device__ inline float rvq_sumsq(const u32x4_t& r, float acc) {               /
     acc = fmaf(lo, lo, acc); acc = fmaf(hi, hi, acc);
   }
   return acc;
+}
+
+// The four lanes that share a vector are 16 lanes (one row) apart.  v_permlane16_swap / v_permlane32_swap hand a lane its own
+// value and that of its partner across rows (l ^ 16, l ^ 32) in an order that is the same for both partners, so any symmetric
+// function of the pair leaves both with the same result - at vector-ALU speed, where a shuffle goes through LDS.
+template <int kRows>
+__device__ __attribute__((always_inline)) inline void rvq_pair(unsigned v, unsigned& a, unsigned& b) {
+  if constexpr (kRows == 16) { const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false); a = r[0]; b = r[1]; }
+  else { const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false); a = r[0]; b = r[1]; }
+}
+__device__ __attribute__((always_inline)) inline float rvq_sum4(float v) {       // sum over the vector's four lanes
+  unsigned a, b;
+  rvq_pair<16>(__float_as_uint(v), a, b); v = __uint_as_float(a) + __uint_as_float(b);
+  rvq_pair<32>(__float_as_uint(v), a, b); return __uint_as_float(a) + __uint_as_float(b);
+}
+__device__ __attribute__((always_inline)) inline float rvq_max4(float v) {
+  unsigned a, b;
+  rvq_pair<16>(__float_as_uint(v), a, b); v = fmaxf(__uint_as_float(a), __uint_as_float(b));
+  rvq_pair<32>(__float_as_uint(v), a, b); return fmaxf(__uint_as_float(a), __uint_as_float(b));
 }
 
 // ---- exact decisions for the vectors whose float32 lead was inside the rounding margin.  Done by the whole workgroup at
@@ -156,8 +178,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
       ra[rb][ks] = *reinterpret_cast<const u32x4_t*>(x + (int64_t)v * kRvqD + ks * 32 + kq * 8);
       a = rvq_sumsq(ra[rb][ks], a);
     }
-    a += __shfl_xor(a, 16); a += __shfl_xor(a, 32);
-    rn2[rb] = a;
+    rn2[rb] = rvq_sum4(a);
   }
 
   const int nch = S / kRvqChunk, total = N * nch;
@@ -354,7 +375,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         const int e = sv[rb][0] == b ? 0 : sv[rb][1] == b ? 1 : sv[rb][2] == b ? 2 : 3;
         bidx[rb] = 16 * bblk[rb] + e;
       }
-      const float cm = fmaxf(fmaxf(cmax2, __shfl_xor(cmax2, 16)), __shfl_xor(fmaxf(cmax2, __shfl_xor(cmax2, 16)), 32));
+      const float cm = rvq_max4(cmax2);
       const bf16_t* stage_cb = cb + (int64_t)stage * S * kRvqD;
       // The winner is certain when its lead over every other score exceeds what rounding can have done to two scores.  The
       // scores that come within that margin are of two kinds.  Those of the lane's kept block have known entries (near[rb]: one
@@ -367,23 +388,30 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
       for (int rb = 0; rb < 4; ++rb) {
         float b = best[rb];
         int bi = bidx[rb] + 4 * kq;
-#pragma unroll
-        for (int o = 16; o < 64; o <<= 1) {
-          const float ob = __shfl_xor(b, o);
-          const int oi = __shfl_xor(bi, o);
-          if (ob > b || (ob == b && oi < bi)) bi = oi;
-          b = fmaxf(b, ob);
+        {
+          unsigned ba, bb, ia, ib;
+          rvq_pair<16>(__float_as_uint(b), ba, bb); rvq_pair<16>((unsigned)bi, ia, ib);
+          bool tb = __uint_as_float(bb) > __uint_as_float(ba) || (__uint_as_float(bb) == __uint_as_float(ba) && (int)ib < (int)ia);
+          b = __uint_as_float(tb ? bb : ba); bi = (int)(tb ? ib : ia);
+          rvq_pair<32>(__float_as_uint(b), ba, bb); rvq_pair<32>((unsigned)bi, ia, ib);
+          tb = __uint_as_float(bb) > __uint_as_float(ba) || (__uint_as_float(bb) == __uint_as_float(ba) && (int)ib < (int)ia);
+          b = __uint_as_float(tb ? bb : ba); bi = (int)(tb ? ib : ia);
         }
         z[rb] = bi;
         bestm[rb] = b;
-        margin[rb] = kRvqGamma2 * (sqrtf(rn2[rb] * 1.0001f * cm) + 0.5f * cm);
+        margin[rb] = kRvqGamma2 * (sqrtf(rn2[rb] * 1.02f * cm) + 0.5f * cm);   // (1.02: rn2 is known to one part in 2^7)
         int nr = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) nr |= (!(b - sv[rb][q] > margin[rb]) ? 1 : 0) << q;
         near[rb] = nr;
         int cnt = __builtin_popcount(nr), unk = !(b - second[rb] > margin[rb]) ? 1 : 0;
-        cnt += __shfl_xor(cnt, 16); cnt += __shfl_xor(cnt, 32);
-        unk |= __shfl_xor(unk, 16); unk |= __shfl_xor(unk, 32);
+        {                                                  // both at once: the count in the low half, the flag above it
+          unsigned a2, b2;
+          unsigned cu = (unsigned)cnt | ((unsigned)unk << 16);
+          rvq_pair<16>(cu, a2, b2); cu = a2 + b2;
+          rvq_pair<32>(cu, a2, b2); cu = a2 + b2;
+          cnt = (int)(cu & 0xffffu); unk = (int)(cu >> 16);
+        }
         amb_any[rb] = unk != 0;
         amb_known[rb] = unk == 0 && cnt != 1;
 #ifdef RVQ_MEASURE_WITHOUT_EXACT_PATH                       // timing probes only: never defined in the library build
@@ -563,11 +591,9 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
           const u32x4_t cz = *reinterpret_cast<const u32x4_t*>(stage_cb + (int64_t)z[rb] * kRvqD + ks * 32 + kq * 8);
-          ra[rb][ks] = rvq_sub_bf16(ra[rb][ks], cz);
-          a = rvq_sumsq(ra[rb][ks], a);
+          ra[rb][ks] = rvq_sub_bf16(ra[rb][ks], cz, a);
         }
-        a += __shfl_xor(a, 16); a += __shfl_xor(a, 32);
-        rn2[rb] = a;
+        rn2[rb] = rvq_sum4(a);
         best[rb] = NEG; second[rb] = NEG; bblk[rb] = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) sv[rb][e] = NEG;
