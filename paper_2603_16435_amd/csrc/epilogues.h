@@ -219,7 +219,8 @@ struct EpiFwdStash {
   template <class L, int MB, int NB, int BM, int BN, int WAVES_M, int WAVES_N, bool AGPR>
   __device__ __attribute__((always_inline)) void run(typename L::acc_t (&acc)[MB][NB], const TileCtx& c, unsigned char* smem, const GemmDims& d, const Pre& pre) const {
     static_assert(L::kBlk == 16 && MB == 8 && NB == 8 && sizeof(T) == 2, "hot kernel only");
-    float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN]
+    float2* red = reinterpret_cast<float2*>(smem);              // [WAVES_M][BN + BN / 32]
+    constexpr int kRedRow = BN + BN / 32;
     const int g = c.lane >> 4, cc = c.lane & 15;
     float rl[NB], sm[NB], su[NB];
 #pragma unroll
@@ -231,18 +232,21 @@ struct EpiFwdStash {
     for (int bj = 0; bj < NB; ++bj) {
 #pragma unroll
       for (int off = 16; off < 64; off <<= 1) { sm[bj] += __shfl_xor(sm[bj], off); su[bj] += __shfl_xor(su[bj], off); }
-      // (slot 16 bj + cc of the wavefront's 128 columns, not column 8 cc + bj: the sixteen lanes then write neighbouring slots)
-      if (c.lane < 16) red[c.wm * BN + c.wn * (BN / WAVES_N) + bj * 16 + cc] = make_float2(sm[bj], su[bj] * zs);
+      // (one spare slot after every 32 columns: the sixteen lanes write columns 8 apart, 64 bytes, and would otherwise meet
+      // in the LDS banks four at a time)
+      if (c.lane < 16) {
+        const int col = c.wn * (BN / WAVES_N) + perm_col(bj, cc);
+        red[c.wm * kRedRow + col + (col >> 5)] = make_float2(sm[bj], su[bj] * zs);
+      }
     }
     __syncthreads();
     if (c.tid < BN) {
       const int n = c.tile_n * BN + c.tid;
       if (n < c.Nv) {
-        static_assert(BN / WAVES_N == 128, "slot numbering of the staging array");
-        const int slot = (c.tid & ~127) + (c.tid & 7) * 16 + ((c.tid & 127) >> 3);
+        const int slot = c.tid + (c.tid >> 5);
         float2 r = red[slot];
 #pragma unroll
-        for (int w = 1; w < WAVES_M; ++w) { const float2 o2 = red[w * BN + slot]; r.x += o2.x; r.y += o2.y; }
+        for (int w = 1; w < WAVES_M; ++w) { const float2 o2 = red[w * kRedRow + slot]; r.x += o2.x; r.y += o2.y; }
         part[(int64_t)c.tile_m * ldp + n] = r;
       }
     }
