@@ -231,7 +231,9 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
  * codebook groups (one per layer / head / cache type) and each of its L vectors x (D = 128 values, bf16):
  *     for i = 0..N-1:   codes[i] = argmin_s || r - c[i][s] ||^2  (lowest index on ties),   r <- bf16(r - c[i][codes[i]]),
  * starting from r = x, where c[i][s] are the effective entries of codebook i (the paper's W_i q_s, stored already
- * projected) and the running residual is kept in the 16-bit storage precision between stages.
+ * projected) and the running residual is kept in the 16-bit storage precision between stages.  The arg-min is the one
+ * exact arithmetic gives on the stored values: scores are computed in float32 on the matrix cores, and every decision
+ * whose lead is within the rounding bound of those scores is settled from the bf16 values in float64.
  *   vectors   [G][L][D] bf16, 16-byte aligned;       codebooks [G][N][S][D] bf16, 16-byte aligned;
  *   norms     [G][N][S] f32: squared norms of the entries, as written by rl_rvq_codebook_norms (once per codebook set);
  *   codes     [G][L][N] int32, overwritten (each in [0, S));

@@ -56,8 +56,8 @@ rl_status rl_debug_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t group_m,
                               int32_t* workgroups, int32_t* tile);
 
 /* rl_rvq_encode that also counts, in the device word *n_exact (added to, not cleared; may be NULL), the decisions whose
- * float32 lead was within the rounding margin and that were therefore re-evaluated exactly in float64 against every
- * entry of the stage (once per wavefront and decision; the last block of a group re-evaluates its padding lanes too).
+ * float32 lead was within the rounding margin and that were therefore settled in float64 among the entries that came
+ * within that margin (counted once per decision; the last workgroup of a group counts its padding lanes too).
  * For tests of that path and for its cost in profiles. */
 rl_status rl_rvq_encode_counted(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,
                                 int32_t N, int32_t S, int32_t* codes, void* residual, int32_t* n_exact, void* stream);
