@@ -5,25 +5,30 @@
 //
 // with the lowest index winning ties and the running residual kept in the cache's 16-bit storage precision.
 //
-// Mapping to the hardware.  A workgroup of four wavefronts takes 256 vectors of one codebook group and walks all N
-// stages with the residuals in registers, already in MFMA operand layout (a lane holds vector l%16 of a block of 16,
-// 8 consecutive k).  A stage's codebook (S x 128 bf16) streams through LDS in chunks of 64 entries (16 KiB, two stages,
-// filled by global -> LDS loads one chunk ahead).  The scores are computed ENTRY-major: A = 16 entries, B = 16 vectors,
-// so that in the accumulator layout a lane owns ONE vector per block and four entries of it.  A lane then keeps one
-// running (best score, second-best score, index) triple per vector block - four triples in all, whatever S is - updated
-// with four vector operations per score (compare, median-of-three, select, max; the index operand is uniform over the
-// wavefront), and at the end of a stage the four lanes that share a vector merge their triples with two exchanges; the
-// winner's index is then already in the lanes that hold that vector's residual.  The accumulators of a block of 16
-// entries start at -|c|^2/2 through the MFMA's C operand, and the blocks of a chunk are software-pipelined: the updates
-// of block c run under the MFMAs of block c+1.
+// Mapping to the hardware.  A workgroup of eight wavefronts (four when a group has at most 256 vectors) takes 64 vectors
+// per wavefront of one codebook group and walks all N stages with the residuals in registers, already in MFMA operand
+// layout (a lane holds vector l%16 of a block of 16, 8 consecutive k).  A stage's codebook (S x 128 bf16) streams through
+// LDS in chunks of 64 entries (16 KiB; three stages, filled by global -> LDS loads two chunks ahead).  The scores are
+// computed ENTRY-major: A = 16 entries, B = 16 vectors, so that in the accumulator layout a lane owns ONE vector per block
+// and four entries of it.  The accumulators of a block of 16 entries start at -|c|^2/2 through the MFMA's C operand, and the
+// blocks of a chunk are software-pipelined: the bookkeeping of block c runs under the MFMAs of block c+1.
+// Running arg-max.  MFMA and vector instructions leave through the same issue port of a SIMD (4 cycles each, a 16x16x32 MFMA
+// lasts 16), so the bookkeeping per score decides the speed.  A lane therefore keeps its state per BLOCK of four scores (its
+// four entries of a 16-entry block): the largest block maximum so far, the number of the block it came from and that
+// block's four scores, and the second-largest block maximum - ten vector operations per four scores, where a compare and two
+// selects per score take sixteen.  Which of the four scores won is looked up once per stage, and the four lanes that share a
+// vector merge with two row swaps; the winner's index is then already in the lanes that hold that vector's residual.
 //
 // Exactness.  The scores come out of f32 accumulation, the definition is exact.  Products of bf16 values are exact in
 // f32, so a score differs from its exact value by at most g (|r| |c| + |c|^2 / 2) with g = 2^-16 (256 roundings of
 // relative size 2^-24 would be needed to exceed it; a score goes through about 160).  If the best f32 score of a vector
-// leads the second best by more than 2 g (|r| c_max + c_max^2 / 2), the winner is the exact arg-max.  Otherwise
-// (about one decision in a thousand, and always for duplicated entries) the wavefront re-evaluates that vector against
-// all S entries in float64 straight from the definition, sum_d (r_d - c_d)^2, smallest distance first, lowest index on
-// ties.  The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.
+// leads every other by more than the margin 2 g (|r| c_max + c_max^2 / 2), the winner is the exact arg-max.  Otherwise
+// (about one decision in 600, and always for duplicated entries) the decision is taken in float64 straight from the
+// definition, sum_d (r_d - c_d)^2 on the stored bf16 values, smallest distance first, lowest index on ties, among the
+// entries whose score came within the margin: those are the only ones that can be the exact arg-min.  When they all lie in
+// the lanes' kept blocks their entries are known and the wavefront settles the vector by itself; when a lane's second-best
+// block maximum is that close, an entry nobody kept is in play and the workgroup looks at the whole stage again (below).
+// The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.
 // LDS layout: entry e at 256 e, its 16-byte piece p at slot p ^ (e & 15): fragment reads are conflict-free.
 #pragma once
 #include "gemm_nt.h"
@@ -97,10 +102,10 @@ __device__ __attribute__((always_inline)) inline float rvq_max4(float v) {
   rvq_pair<32>(__float_as_uint(v), a, b); return fmaxf(__uint_as_float(a), __uint_as_float(b));
 }
 
-// ---- exact decisions for the vectors whose float32 lead was inside the rounding margin.  Done by the whole workgroup at
-// the end of a stage, up to 16 such vectors at a time (there is one in every second or third stage of a workgroup):
+// ---- exact decisions by the whole workgroup, for the vectors with a near score whose entry nobody kept.  At the end of a
+// stage, up to 16 such vectors at a time (there is one in every fifth stage or so of a workgroup):
 //  1. The vectors become the 16 columns of an MFMA B operand and the float32 scores r . c - |c|^2 / 2 of all S entries
-//     are recomputed on the matrix cores, a quarter of the entries per wavefront, fetched straight from memory in
+//     are recomputed on the matrix cores, an equal share of the entries per wavefront, fetched straight from memory in
 //     operand layout, four groups of 16 entries in flight.
 //  2. An entry within the vector's margin (twice the bound on a score's error) of the largest score could be the exact
 //     arg-max; no other entry can.  The largest recomputed score is at least the main pass's best score minus the margin
@@ -143,9 +148,9 @@ template <int kW>
 __global__ __launch_bounds__(64 * kW, 8 / kW)
 void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ cb, const float* __restrict__ cn,
                        int G, int L, int N, int S, int32_t* __restrict__ codes, bf16_t* __restrict__ residual, int32_t* __restrict__ stats) {
-  // three stages of a chunk each: chunk t is computed on while chunks t+1 and t+2 are on their way (one chunk ahead, the
-  // wait for it at the end of every chunk costs about a memory latency: measured, the MFMA-only loop ran at half speed)
-  // The fragment reads of the main loop are inline assembly with the wavefront's own waits (lds_read16 / lds_wait below): the
+  // three stages of a chunk each: chunk t is computed on while chunks t+1 and t+2 are on their way (with one chunk ahead
+  // only, the wait for it at the end of every chunk costs about a memory latency: the MFMA-only loop ran at half speed)
+  // The fragment reads of the main loop are inline assembly with the wavefront's own waits (read1 / lds_wait below): the
   // compiler, seeing a read of an LDS array that loads in flight may write to, would wait for all of them before every read.
   __shared__ __attribute__((aligned(1024))) unsigned char bufs[3][kRvqChunk * 256];
   __shared__ __attribute__((aligned(256))) float nrms[3][kRvqChunk];
@@ -182,17 +187,13 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   }
 
   const int nch = S / kRvqChunk, total = N * nch;
-#ifdef RVQ_PROBE_STAGGER                                 // timing probe: some workgroups start late by RVQ_PROBE_STAGGER_SLEEPS x ~4 us
-  if (((w >> 3) >> RVQ_PROBE_STAGGER) & 1)
-    for (int i = 0; i < RVQ_PROBE_STAGGER_SLEEPS; ++i) __builtin_amdgcn_s_sleep(127);
-#endif
   // staging: chunk t of the linear sequence (stage t / nch, chunk t % nch; consecutive in memory) goes straight from
-  // global memory into LDS.  Wavefront w, load j writes pieces q = 64 (4 j + w) + l: entry q / 16, LDS slot q % 16,
-  // which holds source piece slot ^ (entry & 15); wavefront 0 also brings the chunk's 64 squared norms.
-  // (entry & 15 = (4 w + l/16) & 15 does not depend on j: one lane offset serves all four loads, 16 entries apart)
+  // global memory into LDS in sixteen loads of 1 KiB, 16 / kW per wavefront.  Wavefront w, load j writes pieces
+  // q = 64 (kW j + w) + l: entry q / 16 = 4 (kW j + w) + l/16, LDS slot q % 16, which holds source piece slot ^ (entry & 15).
+  // (entry & 15 = (4 w + l/16) & 15 does not depend on j: one lane offset serves all of a wavefront's loads)
   const unsigned lane_off = (unsigned)((4 * wave + kq) * kRvqD + 8 * (e16 ^ ((4 * wave + kq) & 15)));
-  // load j (of four) of chunk t; the loads of the next chunk are issued one per block of the current one, because a
-  // global -> LDS load stalls its wavefront longest when all four wavefronts issue at the same moment
+  // load j of chunk t; the loads of the chunk after next are issued one per block of the current one (kW = 8: in blocks 0
+  // and 2), because a global -> LDS load stalls its wavefront longest when many wavefronts issue one at the same moment
   auto stage_in1 = [&](int t, int j, unsigned loff, unsigned ln, unsigned char* dst, float* ndst) __attribute__((always_inline)) {
     const bf16_t* base = cb + (int64_t)t * kRvqChunk * kRvqD;
     load16_to_lds(base + 4 * kW * j * kRvqD + loff, dst + 64 * (kW * j + wave) * 16);
@@ -249,9 +250,9 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
     // element e of acc[rb] is the score of entry 16 c + 4 (l/16) + e against vector 16 rb + l%16.
     // The four blocks of a chunk are software-pipelined by hand, one region per block (the scheduler may not move
     // instructions across a region border, which also keeps it from hoisting every read of the chunk to the top and running
-    // out of registers): region c holds the fragment and norm reads of block c+1, one load of the next chunk, the 16 MFMAs
-    // of block c and the 64 running-best updates of block c-1 (region 0: of the previous chunk's last block), and inside a
-    // region the order is pinned to one MFMA, four updates, one MFMA, ...: a wavefront alone then keeps both pipelines busy.
+    // out of registers): region c holds the fragment and norm reads of block c+1, one load of the chunk after next, the 16
+    // MFMAs of block c and the bookkeeping of block c-1 (region 0: of the previous chunk's last block), and inside a region
+    // the order is pinned to one MFMA, two or three vector operations, one MFMA, ...
     floatx4 acc[2][4];
     u32x4_t fa[2][4], nqr[2];
     // LDS offsets of the lane's fragment pieces, derived from the lane number inside the loop (a handful of operations per
@@ -333,7 +334,6 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
 #ifndef RVQ_PROBE_NO_DMA
         if (i == 6 && (kW == 4 || (c & 1) == 0)) stage_in1(tn, kW == 4 ? c : c >> 1, loff, (unsigned)lq, nxt, nnxt);
 #endif
-        // score e = i / 4 of vector block i % 4 of the previous block (region 0: of the previous chunk's last block)
         // part i % 4 of folding in the previous block's scores for vector block i / 4 (region 0: the previous chunk's last block)
         fold(i >> 2, i & 3, c == 0 ? tail[i >> 2] : acc[(c - 1) & 1][i >> 2], ch * 4 + c - 1);
         __builtin_amdgcn_sched_barrier(0);
