@@ -28,7 +28,9 @@
 // entries whose score came within the margin: those are the only ones that can be the exact arg-min.  When they all lie in
 // the lanes' kept blocks their entries are known and the wavefront settles the vector by itself; when a lane's second-best
 // block maximum is that close, an entry nobody kept is in play and the workgroup looks at the whole stage again (below).
-// The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.
+// The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.  (The bound is
+// relative: it assumes that products and partial sums stay in float32's normal range - no underflow, no overflow - which holds
+// for any cache values of interest, |x| between 1e-15 and 1e15, say.)
 // LDS layout: entry e at 256 e, its 16-byte piece p at slot p ^ (e & 15): fragment reads are conflict-free.
 #pragma once
 #include "gemm_nt.h"
