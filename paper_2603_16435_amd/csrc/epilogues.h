@@ -39,6 +39,7 @@ struct EpiFwd {
   typedef NoPre Pre;
   template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = false;
+  static constexpr bool kGatherB = true;      // the B rows come through a row map (GemmDims::b_rows)
   __device__ void keep_alive() const { zy_c[0] = 0.f; }
   const int* ids_c;     // [chunk-global compact row] sampled token
   float* zy_c;          // [compact row] target logit
@@ -166,6 +167,7 @@ struct EpiFwdStash {
     return p;
   }
   static constexpr bool kPermute = true;
+  static constexpr bool kGatherB = true;      // the B rows come through a row map (GemmDims::b_rows)
   __device__ void keep_alive() const { E[0] = (T)0.f; }
   const float* ref_l2e;   // [compact row] ref_t * log2(e)
   float2* part;           // [tiles_m(V)][ldp] partial (s, u) per token of the chunk
@@ -280,6 +282,7 @@ struct EpiDS {
   typedef NoPre Pre;
   template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = true;
+  static constexpr bool kGatherB = true;      // the B rows come through a row map (GemmDims::b_rows)
   __device__ void keep_alive() const { dS[0] = (T)0.f; }
   const int* ids_c; const float* lse_c; const float* c_c;
   T* dS;  int64_t ld_ds;    // [chunk rows][Vp]
@@ -373,6 +376,7 @@ struct EpiDX {
   typedef NoPre Pre;
   template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = false;
+  static constexpr bool kGatherB = false;      // the B rows come through a row map (GemmDims::b_rows)
   __device__ void keep_alive() const { dX[0] = (T)0.f; }
   const int* row_map;   // compact row -> original row
   T* dX; int64_t ldx; int H;
@@ -405,6 +409,7 @@ struct EpiDW {
   typedef NoPre Pre;
   template <class L> __device__ Pre preload(const TileCtx&, const GemmDims&) const { return Pre(); }
   static constexpr bool kPermute = false;
+  static constexpr bool kGatherB = false;      // the B rows come through a row map (GemmDims::b_rows)
   __device__ void keep_alive() const { dW[0] = 0.f; }
   float* dW; int64_t ldw; int V, H; int accumulate;
 

@@ -309,6 +309,21 @@ void gemm_nt_kernel(const T* __restrict__ A, const T* __restrict__ B, GemmDims d
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
+// The same load with its address given as a wavefront-uniform base (two scalar registers) plus a 32-bit lane offset in
+// bytes: no vector operation goes into the address.  Written as inline assembly because the compiler, given base + offset,
+// folds the offset into a per-lane 64-bit pointer outside the loop and adds the slab's stride to it with a vector add per
+// load.  It keeps no count of such a load: the waits that cover it are the ones written out in the main loop.
+__device__ __attribute__((always_inline)) inline void load16_to_lds_uniform(const void* base, unsigned lane_bytes, void* l) {
+  const unsigned lds = (unsigned)(size_t)(lds_ptr_t)l;      // uniform
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(lane_bytes), "s"(base), "s"(lds) : "memory");
+}
+// ... and with a 64-bit address per lane, for rows that come through a row map.  (Every load of the hot kernel's main loop is
+// one of these two, so that the compiler itself never sets M0 there.)
+__device__ __attribute__((always_inline)) inline void load16_to_lds_lanes(const void* g, void* l) {
+  const unsigned lds = (unsigned)(size_t)(lds_ptr_t)l;      // uniform
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(g), "s"(lds) : "memory");
+}
+
 __device__ inline void load16_to_lds(const void* g, void* l) {   // 64 lanes x 16 B -> 1 KiB of LDS at l
   __builtin_amdgcn_global_load_lds((glb_ptr_t)g, (lds_ptr_t)l, 16, 0, 0);
 }
@@ -391,8 +406,17 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   // ---- slab staging.  Wavefront w fills rows [64w, 64w+64) of A and of B: eight loads of eight
   // rows each.  A load writes lane l's 16 bytes to LDS offset 16*l of its 1 KiB target, i.e. row
   // l/8, slot l%8; the swizzle is therefore applied on the global side (which chunk a lane fetches).
+  // An operand whose rows are where they are numbered (every one but the hidden states, whose rows come through the row
+  // map) is addressed as a wavefront-uniform base plus a 32-bit lane offset: the address of a load is then a scalar add per
+  // slab and no vector operation (vector operations and MFMAs take turns on a SIMD).  All rows of a tile lie within
+  // 256 rows of the tile's first, so the offsets fit.
+  constexpr bool GB = Epi::kGatherB;
   const bf16_t* ap[8];
   const bf16_t* bp[8];
+  unsigned aoff[8], boff[8];
+  const bf16_t* const abase = ATR ? A + tiled_index(0, tm * BM, d.lda)
+                                  : A + (d.a_tiled ? tiled_index(tm * BM, 0, d.K) : (int64_t)(tm * BM) * d.lda);
+  const bf16_t* const bbase = B + (d.b_tiled ? tiled_index(tn * BN, 0, d.K) : (int64_t)(tn * BN) * d.ldb);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int lr = wave * 64 + j * 8 + (lane >> 3);
@@ -412,6 +436,8 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
     r = tn * BN + (Epi::kPermute ? perm_lds_row_b(lr) : lr); r = r < N ? r : N - 1;
     if (d.b_rows) r = d.b_rows[r];
     bp[j] = B + (d.b_tiled ? tiled_index(r, 0, d.K) : (int64_t)r * d.ldb) + c * 8;
+    aoff[j] = (unsigned)(ap[j] - abase) * 2u;                   // in bytes
+    boff[j] = GB ? 0u : (unsigned)(bp[j] - bbase) * 2u;
   }
   const int a_ks = d.a_tiled ? 16384 : BK, b_ks = d.b_tiled ? 16384 : BK;     // elements from one slab to the next
   // K-major A: slab s is k-rows [64 s, 64 s + 64), i.e. quarter s%4 of row block s/4 of the tiled layout
@@ -421,8 +447,12 @@ __device__ __attribute__((always_inline)) inline void gemm_nt_bf16_tile(const bf
   // load j of the 16 per slab (0..7 = A rows, 8..15 = B rows)
   auto issue1 = [&](int slab, unsigned char* stage, int j) __attribute__((always_inline)) {
     unsigned char* as = stage + wave * 64 * kSlabBytes;
-    if (j < 8) load16_to_lds(ap[j] + a_slab(slab), as + j * 8 * kSlabBytes);
-    else load16_to_lds(bp[j - 8] + (int64_t)slab * b_ks, as + A_BYTES + (j - 8) * 8 * kSlabBytes);
+    if (j < 8) {
+      load16_to_lds_uniform(abase + a_slab(slab), aoff[j], as + j * 8 * kSlabBytes);   // (the hot kernel is not launched with gathered A rows)
+    } else {
+      if constexpr (GB) load16_to_lds_lanes(bp[j - 8] + (int64_t)slab * b_ks, as + A_BYTES + (j - 8) * 8 * kSlabBytes);
+      else load16_to_lds_uniform(bbase + (int64_t)slab * b_ks, boff[j - 8], as + A_BYTES + (j - 8) * 8 * kSlabBytes);
+    }
   };
 
   // ---- L2 prefetch.  The workgroups resident on one XCD at a time form (about) a block of 8 M-tiles

@@ -816,7 +816,8 @@ template <class Tune, class Epi>
 static void launch_gemm(const bf16_t* A, const bf16_t* B, const GemmDims& d, const Epi& epi, hipStream_t s) {
   const int tiles = launch_tiles((d.M + kBM - 1) / kBM, (d.N + kBN - 1) / kBN);
   const bool fast = (d.K % 128 == 0) && (d.lda % 8 == 0) && (d.ldb % 8 == 0) &&
-                    ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0);
+                    ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) % 16 == 0) &&
+                    !d.a_rows && (d.b_rows != nullptr) == Epi::kGatherB;     // (how the hot kernel addresses its operands)
   if (!fast) { launch_generic<bf16_t, Epi>(A, B, d, epi, tiles, s); return; }
   gemm_nt_bf16_kernel<Epi, Tune><<<tiles, 256, 0, s>>>(A, B, d, epi);
 }
