@@ -25,8 +25,8 @@ PEAK_F32_TFLOPS = 157.3
 # of the largest launch of each contraction class on the default workload, from two rocprofv3 --pmc runs per
 # backward mode whose summary is profiles/gemm_nt_bf16_7b.md.  Counters cannot be read live, so these are constants of that run.
 MEASURED_TRAFFIC_7B = {        # default chunks: 40960 rows single-pass ("stash"), 32768 rows recompute
-    "stash": {"gemm_fwd": 90.7e9 + 12.7e9, "gemm_bwd": 188.9e9 + 2.5e9},
-    "recompute": {"gemm_fwd": 56.3e9 + 0.3e9, "gemm_ds": 68.3e9 + 10.0e9, "gemm_dx": 57.6e9 + 0.2e9, "gemm_dw": 83.4e9 + 2.2e9},
+    "stash": {"gemm_fwd": 96.4e9 + 12.7e9, "gemm_bwd": 198.3e9 + 2.5e9},
+    "recompute": {"gemm_fwd": 53.6e9 + 0.3e9, "gemm_ds": 57.4e9 + 10.0e9, "gemm_dx": 61.8e9 + 0.2e9, "gemm_dw": 85.1e9 + 2.2e9},
 }
 CPU_SAMPLE_LEN_DIV = {"tiny": 1, "small": 8, "7b": 160, "long": 640, "32b": 768}   # ~10-30 s of oracle work
 
