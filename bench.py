@@ -128,9 +128,9 @@ def bench_rvq_encode(a, dev):
            "config": {"workload": f"key-cache window of the paper's 8B setting: G={G} groups x L={L} vectors, D={D}, N={N} stages of S={S} entries "
                                   "(synthetic Gaussian codebooks; no trained ones exist here)"},
            "roofline": {"bound": "mfma", "kernel": "rvq_encode_kernel", "achieved": flops / sec / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                        "frac": flops / sec / 1e12 / PEAK_BF16_TFLOPS, "traffic": 4.5e9,
+                        "frac": flops / sec / 1e12 / PEAK_BF16_TFLOPS, "traffic": 3.2e9,
                         "traffic_note": "rocprofv3 FETCH_SIZE of one launch, scaled x2.0 (profiles/rvq_encode_8b_key.md); the 0.06 GB of codes and residuals written are not in it",
-                        "note": "2 L S D N flop per group; with K = D = 128 every MFMA needs ten issue cycles of arg-max bookkeeping on the same port: "
+                        "note": "2 L S D N flop per group; with K = D = 128 every MFMA needs eleven issue cycles of arg-max bookkeeping on the same port: "
                                 "issue-bound, not power-bound (profiles/rvq_encode_8b_key.md)"}}
     if not a.no_cpu_baseline:
         from oracle import rvq_oracle as rvq

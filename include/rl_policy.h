@@ -238,7 +238,7 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
  *   norms     [G][N][S] f32: squared norms of the entries, as written by rl_rvq_codebook_norms (once per codebook set);
  *   codes     [G][L][N] int32, overwritten (each in [0, S));
  *   residual  [G][L][D] bf16 or NULL: what is left of each vector after the N stages.
- * D must be 128 and S a multiple of 64 (else RL_ERR_SHAPE).  All pointers are device pointers; the calls allocate
+ * D must be 128 and S a multiple of 64, at most 65536 (else RL_ERR_SHAPE).  All pointers are device pointers; the calls allocate
  * nothing, do not synchronise, and enqueue on `stream`. */
 rl_status rl_rvq_codebook_norms(const void* codebooks, int32_t G, int32_t N, int32_t S, int32_t D, float* norms, void* stream);
 rl_status rl_rvq_encode(const void* vectors, const void* codebooks, const float* norms, int32_t G, int64_t L, int32_t D,

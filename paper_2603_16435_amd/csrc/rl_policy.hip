@@ -1340,7 +1340,7 @@ rl_status rl_logz_head_backward(const float* d_log_z, int32_t P, int32_t H, int3
 // ------------------------------------------------------------------ residual-VQ encode
 static rl_status rvq_check(int32_t G, int64_t L, int32_t D, int32_t N, int32_t S) {
   if (G < 1 || G > 65535 || L < 1 || L > ((int64_t)1 << 24) || N < 1 || S < 1) return RL_ERR_SHAPE;
-  if (D != kRvqD || (S % kRvqChunk) != 0 || (int64_t)N * S > ((int64_t)1 << 26)) return RL_ERR_SHAPE;
+  if (D != kRvqD || (S % kRvqChunk) != 0 || S > 65536 || (int64_t)N * S > ((int64_t)1 << 26)) return RL_ERR_SHAPE;
   return RL_OK;
 }
 

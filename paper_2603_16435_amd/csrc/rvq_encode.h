@@ -14,23 +14,25 @@
 // blocks of a chunk are software-pipelined: the bookkeeping of block c runs under the MFMAs of block c+1.
 // Running arg-max.  MFMA and vector instructions leave through the same issue port of a SIMD (4 cycles each, a 16x16x32 MFMA
 // lasts 16), so the bookkeeping per score decides the speed.  A lane therefore keeps its state per BLOCK of four scores (its
-// four entries of a 16-entry block): the largest block maximum so far, the number of the block it came from and that
-// block's four scores, and the second-largest block maximum - ten vector operations per four scores, where a compare and two
-// selects per score take sixteen.  Which of the four scores won is looked up once per stage, and the four lanes that share a
-// vector merge with two row swaps; the winner's index is then already in the lanes that hold that vector's residual.
+// four entries of a 16-entry block): the three largest block maxima so far, each carrying the number of its block in its
+// lowest mantissa bits, and the four scores of the best block - eleven vector operations per four scores, where a compare
+// and two selects per score take sixteen.  Which of the four scores won is looked up once per stage, and the four lanes that
+// share a vector merge with two row swaps; the winner's index is then already in the lanes that hold that vector's residual.
 //
 // Exactness.  The scores come out of f32 accumulation, the definition is exact.  Products of bf16 values are exact in
 // f32, so a score differs from its exact value by at most g (|r| |c| + |c|^2 / 2) with g = 2^-16 (256 roundings of
-// relative size 2^-24 would be needed to exceed it; a score goes through about 160).  If the best f32 score of a vector
-// leads every other by more than the margin 2 g (|r| c_max + c_max^2 / 2), the winner is the exact arg-max.  Otherwise
-// (about one decision in 600, and always for duplicated entries) the decision is taken in float64 straight from the
-// definition, sum_d (r_d - c_d)^2 on the stored bf16 values, smallest distance first, lowest index on ties, among the
-// entries whose score came within the margin: those are the only ones that can be the exact arg-min.  When they all lie in
-// the lanes' kept blocks their entries are known and the wavefront settles the vector by itself; when a lane's second-best
-// block maximum is that close, an entry nobody kept is in play and the workgroup looks at the whole stage again (below).
-// The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.  (The bound is
-// relative: it assumes that products and partial sums stay in float32's normal range - no underflow, no overflow - which holds
-// for any cache values of interest, |x| between 1e-15 and 1e15, say.)
+// relative size 2^-24 would be needed to exceed it; a score goes through about 160); a block maximum moves by at most
+// 2^(nb - 23) of itself more when the nb bits of its block number are written into it.  If the best score of a vector
+// leads every other by more than the margin 2 (g + 2^(nb - 23)) (|r| c_max + c_max^2 / 2), the winner is the exact arg-max.
+// Otherwise (about one decision in 400, and always for duplicated entries) the decision is taken in float64 straight from
+// the definition, sum_d (r_d - c_d)^2 on the stored bf16 values, smallest distance first, lowest index on ties, among the
+// entries whose score came within the margin: those are the only ones that can be the exact arg-min.  They are the near
+// scores of the lanes' best blocks (entries known) and, where a lane's second-largest block maximum is that close, the four
+// entries of that block: the wavefront settles the vector among them by itself.  Only when a lane's third-largest block
+// maximum is within the margin as well are there entries nobody can name, and the workgroup looks at the whole stage again
+// (below).  The codes therefore equal the float64 arg-min of the definition, not just a nearest entry up to rounding.  (The
+// bound is relative: it assumes that products and partial sums stay in float32's normal range - no underflow, no overflow -
+// which holds for any cache values of interest, |x| between 1e-15 and 1e15, say.  S <= 65536: block numbers of 12 bits.)
 // LDS layout: entry e at 256 e, its 16-byte piece p at slot p ^ (e & 15): fragment reads are conflict-free.
 #pragma once
 #include "gemm_nt.h"
@@ -104,8 +106,8 @@ __device__ __attribute__((always_inline)) inline float rvq_max4(float v) {
   rvq_pair<32>(__float_as_uint(v), a, b); return fmaxf(__uint_as_float(a), __uint_as_float(b));
 }
 
-// ---- exact decisions by the whole workgroup, for the vectors with a near score whose entry nobody kept.  At the end of a
-// stage, up to 16 such vectors at a time (there is one in every fifth stage or so of a workgroup):
+// ---- exact decisions by the whole workgroup, for the vectors with a near score whose entry nobody can name (rare: three
+// block maxima of one lane within the margin).  At the end of a stage, up to 16 such vectors at a time:
 //  1. The vectors become the 16 columns of an MFMA B operand and the float32 scores r . c - |c|^2 / 2 of all S entries
 //     are recomputed on the matrix cores, an equal share of the entries per wavefront, fetched straight from memory in
 //     operand layout, four groups of 16 entries in flight.
@@ -141,6 +143,26 @@ __device__ __attribute__((always_inline)) inline double rvq_exact_distance(const
   double acc = fma(d1, d1, d0 * d0);
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) acc += __shfl_xor(acc, o);
+  return acc;
+}
+
+// The same for four entries at once, one per group of 16 lanes: lane t of a group takes components 8 t .. 8 t + 7 in order,
+// the 16 partial sums are added in a fixed tree.  ent < 0: no entry for this group (+inf).  All 64 lanes must call it.
+__device__ __attribute__((always_inline)) inline double rvq_exact_distance16(const u32x4_t* bits, const bf16_t* stage_cb, int ent, int t) {
+  double acc = __builtin_inf();
+  if (ent >= 0) {
+    const u32x4_t w = *reinterpret_cast<const u32x4_t*>(stage_cb + (int64_t)ent * kRvqD + 8 * t);
+    const u32x4_t r = bits[t];
+    acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const double d0 = (double)__uint_as_float(r[j] << 16) - (double)__uint_as_float(w[j] << 16);
+      const double d1 = (double)__uint_as_float(r[j] & 0xffff0000u) - (double)__uint_as_float(w[j] & 0xffff0000u);
+      acc = fma(d0, d0, acc); acc = fma(d1, d1, acc);
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) acc += __shfl_xor(acc, o);
   return acc;
 }
 
@@ -219,23 +241,31 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
   // largest block maximum so far, the second largest, the block that holds the largest, and that block's four scores.  Which
   // of the four won, and how close the others of that block came, is looked up once at the end of the stage: ten vector
   // operations per four scores instead of sixteen.
-  float best[4], second[4], sv[4][4], cmax2 = 0.f;
-  int bblk[4];
+  float best[4], second[4], third[4], sv[4][4], cmax2 = 0.f;
   const float NEG = -__builtin_inff();
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
-    best[rb] = NEG; second[rb] = NEG; bblk[rb] = 0;
+    best[rb] = NEG; second[rb] = NEG; third[rb] = NEG;
 #pragma unroll
     for (int e = 0; e < 4; ++e) sv[rb][e] = NEG;
   }
+  // A block maximum carries the number of its block in its lowest mantissa bits (nb bits for S / 16 blocks): the three
+  // largest block maxima a lane keeps then say where they came from, at one vector operation per block instead of selects
+  // for each.  The price is a relative change of the value of at most 2^(nb - 23), which the margin allows for.
+  const int nblk = S / 16;
+  const int nb = 32 - __builtin_clz((unsigned)(nblk - 1));      // S / 16 >= 4 blocks
+  const unsigned idmask = (1u << nb) - 1u, nidmask = ~idmask;
+  const float gamma2 = kRvqGamma2 + __builtin_ldexpf(1.f, nb - 22);   // twice (the rounding bound + the block number's bits)
 
   // scores of the last block of a chunk: folded into the running best under the first MFMAs of the next chunk (at the
-  // start of a stage they are -inf, which changes nothing)
+  // start of a stage they are a finite stand-in for -inf, below every score, which the first real block replaces; -inf
+  // itself would turn into a NaN when a block number is written into its low bits)
+  const float NEGF = -3.0e38f;
   floatx4 tail[4];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) tail[rb][e] = NEG;
+    for (int e = 0; e < 4; ++e) tail[rb][e] = NEGF;
 
   int t = 0, stg = 0;
   for (int stage = 0; stage < N; ++stage) {
@@ -278,23 +308,24 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
       asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(nq));
     };
     // the four scores v of one block folded into the running state of vector block rb, in four parts u (one per MFMA step).
-    // Blocks arrive in increasing order, so a later equal maximum never replaces the block kept.
+    // (Which of two equal maxima is kept does not matter: equal scores are always settled exactly.)
     float m4 = 0.f;
     bool gt = false;
     auto fold = [&](int rb, int u, const floatx4& v, int blk) __attribute__((always_inline)) {
 #ifndef RVQ_PROBE_NO_UPDATE
       if (u == 0) {
-        float m3;
+        float m3, mx;
         asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m3) : "v"(v[0]), "v"(v[1]), "v"(v[2]));
-        asm("v_max_f32 %0, %1, %2" : "=v"(m4) : "v"(m3), "v"(v[3]));     // (written out: fmaxf would canonicalise both inputs first)
+        asm("v_max_f32 %0, %1, %2" : "=v"(mx) : "v"(m3), "v"(v[3]));     // (written out: fmaxf would canonicalise both inputs first)
+        m4 = __uint_as_float((__float_as_uint(mx) & nidmask) | (unsigned)blk);   // the block's number into the low bits
         gt = m4 > best[rb];
       } else if (u == 1) {
-        bblk[rb] = gt ? blk : bblk[rb];
         sv[rb][0] = gt ? v[0] : sv[rb][0];
         sv[rb][1] = gt ? v[1] : sv[rb][1];
       } else if (u == 2) {
         sv[rb][2] = gt ? v[2] : sv[rb][2];
         sv[rb][3] = gt ? v[3] : sv[rb][3];
+        third[rb] = __builtin_amdgcn_fmed3f(second[rb], third[rb], m4);   // (before the second largest moves)
       } else {
         second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], m4);
         asm("v_max_f32 %0, %0, %1" : "+v"(best[rb]) : "v"(m4));
@@ -317,6 +348,8 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         asm("v_max3_f32 %0, %0, %1, %2" : "+v"(cmax2) : "v"(q[0]), "v"(q[1]));
         asm("v_max3_f32 %0, %0, %1, %2" : "+v"(cmax2) : "v"(q[2]), "v"(q[3]));
       }
+      int blkv = (ch * 4 + c - 1) & (int)idmask;     // the block whose scores this region folds in, in a register of its own
+      asm volatile("" : "+v"(blkv));
       __builtin_amdgcn_sched_barrier(0);
       // 16 steps, each fenced off so that the order written is the order issued: one MFMA of block c (k-step i / 4, vector
       // block i % 4), a part of folding the previous block's scores into the running state (two or three vector operations),
@@ -337,7 +370,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         if (i == 6 && (kW == 4 || (c & 1) == 0)) stage_in1(tn, kW == 4 ? c : c >> 1, loff, (unsigned)lq, nxt, nnxt);
 #endif
         // part i % 4 of folding in the previous block's scores for vector block i / 4 (region 0: the previous chunk's last block)
-        fold(i >> 2, i & 3, c == 0 ? tail[i >> 2] : acc[(c - 1) & 1][i >> 2], ch * 4 + c - 1);
+        fold(i >> 2, i & 3, c == 0 ? tail[i >> 2] : acc[(c - 1) & 1][i >> 2], blkv);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -361,28 +394,35 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         const floatx4 v = tail[rb];
         float m3;
         asm("v_max3_f32 %0, %1, %2, %3" : "=v"(m3) : "v"(v[0]), "v"(v[1]), "v"(v[2]));
-        const float m4 = fmaxf(m3, v[3]);
+        const float m4 = __uint_as_float((__float_as_uint(fmaxf(m3, v[3])) & nidmask) | (unsigned)(nch * 4 - 1));
         const bool gt = m4 > best[rb];
-        bblk[rb] = gt ? nch * 4 - 1 : bblk[rb];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { sv[rb][e] = gt ? v[e] : sv[rb][e]; tail[rb][e] = NEG; }
+        for (int e = 0; e < 4; ++e) { sv[rb][e] = gt ? v[e] : sv[rb][e]; tail[rb][e] = NEGF; }
+        third[rb] = __builtin_amdgcn_fmed3f(second[rb], third[rb], m4);
         second[rb] = __builtin_amdgcn_fmed3f(best[rb], second[rb], m4);
         best[rb] = fmaxf(best[rb], m4);
       }
-      // which of the kept block's four scores is the maximum (the first, if several)
-      int bidx[4];
+      // the blocks of the largest and the second-largest block maximum (their low bits), and which of the kept block's four
+      // scores is the maximum (the first, if several)
+      int bidx[4], bblk[4], sblk[4];
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
-        const float b = best[rb];
-        const int e = sv[rb][0] == b ? 0 : sv[rb][1] == b ? 1 : sv[rb][2] == b ? 2 : 3;
+        bblk[rb] = (int)(__float_as_uint(best[rb]) & idmask);
+        sblk[rb] = (int)(__float_as_uint(second[rb]) & idmask);
+        if (bblk[rb] >= nblk) bblk[rb] = 0;               // (only if no score of the stage was a number)
+        if (sblk[rb] >= nblk) sblk[rb] = 0;
+        const float m = fmaxf(fmaxf(sv[rb][0], sv[rb][1]), fmaxf(sv[rb][2], sv[rb][3]));
+        const int e = sv[rb][0] == m ? 0 : sv[rb][1] == m ? 1 : sv[rb][2] == m ? 2 : 3;
         bidx[rb] = 16 * bblk[rb] + e;
       }
       const float cm = rvq_max4(cmax2);
       const bf16_t* stage_cb = cb + (int64_t)stage * S * kRvqD;
-      // The winner is certain when its lead over every other score exceeds what rounding can have done to two scores.  The
-      // scores that come within that margin are of two kinds.  Those of the lane's kept block have known entries (near[rb]: one
-      // bit per score of the block): if these are all there is, the wavefront settles the vector among them by itself.  A lane
-      // whose second-best block maximum comes that close stands for an entry nobody kept: then the whole workgroup looks again.
+      // The winner is certain when its lead over every other score exceeds what rounding (and the block number in the low
+      // bits) can have done to two scores.  What comes within that margin is looked at exactly.  The scores of a lane's kept
+      // block have known entries (bits 0-3 of near[rb]: one per score of the block).  A second-largest block maximum that
+      // close (bit 4) puts the four entries of its block in play, whichever of them it was.  If these are all there is, the
+      // wavefront settles the vector among them by itself.  A lane whose third-largest block maximum comes that close stands
+      // for entries nobody can name: then the whole workgroup looks at the stage again.
       int z[4], near[4];
       bool amb_known[4], amb_any[4];
       float margin[4], bestm[4];
@@ -401,12 +441,13 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
         }
         z[rb] = bi;
         bestm[rb] = b;
-        margin[rb] = kRvqGamma2 * (sqrtf(rn2[rb] * 1.02f * cm) + 0.5f * cm);   // (1.02: rn2 is known to one part in 2^7)
+        margin[rb] = gamma2 * (sqrtf(rn2[rb] * 1.02f * cm) + 0.5f * cm);   // (1.02: rn2 is known to one part in 2^7)
         int nr = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) nr |= (!(b - sv[rb][q] > margin[rb]) ? 1 : 0) << q;
+        if (!(b - second[rb] > margin[rb])) nr |= 16;
         near[rb] = nr;
-        int cnt = __builtin_popcount(nr), unk = !(b - second[rb] > margin[rb]) ? 1 : 0;
+        int cnt = __builtin_popcount(nr & 15) + (nr & 16), unk = !(b - third[rb] > margin[rb]) ? 1 : 0;
         {                                                  // both at once: the count in the low half, the flag above it
           unsigned a2, b2;
           unsigned cu = (unsigned)cnt | ((unsigned)unk << 16);
@@ -438,23 +479,45 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) wvec[wave][ks * 4 + kq] = ra[rb][ks];
           }
+        // its candidates: per lane group eight possible ones (the four scores of the best block, the four entries of the
+        // second block), as one bit each, and the two block numbers
+        unsigned cand = 0;
+        int b1[4], b2[4];
+#pragma unroll
+        for (int kq2 = 0; kq2 < 4; ++kq2) {
+          int m = 0;
+#pragma unroll
+          for (int rb = 0; rb < 4; ++rb) {                   // near bits, best block and second block of lane group kq2, in one word
+            const int mm = __shfl(near[rb] | (bblk[rb] << 5) | (sblk[rb] << 18), ev + 16 * kq2);
+            if (rb == rbs) m = mm;
+          }
+          m = __builtin_amdgcn_readfirstlane(m);
+          b1[kq2] = (m >> 5) & 0x1fff; b2[kq2] = (m >> 18) & 0x1fff;
+          cand |= (unsigned)((m & 15) | ((m & 16) ? 0xf0 : 0)) << (8 * kq2);
+        }
         double dmin = __builtin_inf();
         int imin = 0x7fffffff;
-        for (int kq2 = 0; kq2 < 4; ++kq2) {
-          int m = 0, blk = 0;
+        while (cand) {                                       // four at a time, one per group of 16 lanes
+          int ce[4];
 #pragma unroll
-          for (int rb = 0; rb < 4; ++rb) {
-            const int mm = __shfl(near[rb], ev + 16 * kq2), bb = __shfl(bblk[rb], ev + 16 * kq2);
-            if (rb == rbs) { m = mm; blk = bb; }
+          for (int gq = 0; gq < 4; ++gq) {
+            ce[gq] = -1;
+            if (cand) {
+              const int c = __builtin_ctz(cand);
+              cand &= cand - 1;
+              const int kq2 = c >> 3, q = c & 7;
+              const int blk = q < 4 ? (kq2 == 0 ? b1[0] : kq2 == 1 ? b1[1] : kq2 == 2 ? b1[2] : b1[3])
+                                    : (kq2 == 0 ? b2[0] : kq2 == 1 ? b2[1] : kq2 == 2 ? b2[2] : b2[3]);
+              const int ent = 16 * blk + 4 * kq2 + (q & 3);
+              ce[gq] = (unsigned)ent < (unsigned)S ? ent : -1;   // (always inside: block numbers come from the chunk loop)
+            }
           }
-          m = __builtin_amdgcn_readfirstlane(m); blk = __builtin_amdgcn_readfirstlane(blk);
-          while (m) {
-            const int q = __builtin_ctz(m);
-            m &= m - 1;
-            const int ent = 16 * blk + 4 * kq2 + q;
-            if ((unsigned)ent >= (unsigned)S) continue;      // (cannot happen: block numbers come from the chunk loop)
-            const double d = rvq_exact_distance(&wvec[wave][0], stage_cb, ent, lane);
-            if (d < dmin || (d == dmin && ent < imin)) { dmin = d; imin = ent; }
+          const int mine_c = kq == 0 ? ce[0] : kq == 1 ? ce[1] : kq == 2 ? ce[2] : ce[3];
+          const double d = rvq_exact_distance16(&wvec[wave][0], stage_cb, mine_c, e16);
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const double dg = __shfl(d, 16 * gq);
+            if (ce[gq] >= 0 && (dg < dmin || (dg == dmin && ce[gq] < imin))) { dmin = dg; imin = ce[gq]; }
           }
         }
         if ((unsigned)imin < (unsigned)S) {
@@ -596,7 +659,7 @@ void rvq_encode_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ 
           ra[rb][ks] = rvq_sub_bf16(ra[rb][ks], cz, a);
         }
         rn2[rb] = rvq_sum4(a);
-        best[rb] = NEG; second[rb] = NEG; bblk[rb] = 0;
+        best[rb] = NEG; second[rb] = NEG; third[rb] = NEG;
 #pragma unroll
         for (int e = 0; e < 4; ++e) sv[rb][e] = NEG;
       }
