@@ -186,3 +186,17 @@ def test_tile_order_visits_every_tile_once_and_keeps_dies_balanced(lib, by_share
             assert max(per_die) - min(per_die) <= 1
     assert lib.rl_debug_tile_order(0, 4, 8, 0, C.byref(n), None) == 2
     assert lib.rl_debug_tile_order(4, 4, 8, 0, None, None) == 1
+
+
+def test_rvq_encode_rejects_shapes_it_is_not_written_for(lib):
+    # host checks only: the pointers are never dereferenced (any non-null value will do), nothing is launched
+    p = C.c_void_p(4096)
+    args = lambda D, S, N=4, G=1, L=10: (p, p, p, C.c_int32(G), C.c_int64(L), C.c_int32(D), C.c_int32(N), C.c_int32(S), p, None, None)
+    lib.rl_rvq_encode.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.rl_rvq_encode.restype = C.c_int
+    assert lib.rl_rvq_encode(*args(64, 1024)) == 2           # head dimension other than 128
+    assert lib.rl_rvq_encode(*args(128, 100)) == 2           # S not a multiple of 64
+    assert lib.rl_rvq_encode(*args(128, 131072, N=1)) == 2   # more entries than block numbers of 12 bits can name
+    assert lib.rl_rvq_encode(*args(128, 1024, G=0)) == 2
+    assert lib.rl_rvq_encode(None, p, p, 1, 10, 128, 4, 1024, p, None, None) == 1
