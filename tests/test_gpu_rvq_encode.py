@@ -49,7 +49,8 @@ def _compare(x, cb, codes, res):
                                       (1, 1, 3, 64),         # a single vector, a single chunk per stage
                                       (3, 513, 16, 512),     # the value-cache shape of the paper's 8B setting (N=16, S=512)
                                       (9, 256, 4, 192),      # a full workgroup of four wavefronts; 9 groups (the grid covers 16); S not a power of two
-                                      (1, 257, 2, 64)])      # one vector beyond 256: eight wavefronts, more wavefronts than 16-entry blocks
+                                      (1, 257, 2, 64),       # one vector beyond 256: eight wavefronts, more wavefronts than 16-entry blocks
+                                      (1, 130, 2, 4096)])    # a large codebook: 256 blocks per stage, 8-bit block numbers in the block maxima
 def test_rvq_encode_matches_the_oracle(G, L, N, S):
     x, cb = synth.make_rvq_case(G, L, N, S, device="cuda")
     codes, res = binding.rl_rvq_encode(x, cb)
